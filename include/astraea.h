@@ -1,0 +1,163 @@
+/*
+ * astraea.h - C ABI of the token-wise attention hot path of Astraea
+ * (arXiv 2506.05096) for AMD MI355X (gfx950).
+ *
+ * One layer-step of the method (paper Sec. 3.2; supplementary Algorithm 1) is
+ *     score -> select top-k -> [gather] -> attention of the selected queries
+ *     over all keys/values -> scatter into the cached per-token outputs.
+ * Each call below is one of those steps.  Conventions shared by all calls:
+ *
+ *  - Every tensor pointer is DEVICE memory owned by the caller; the library
+ *    keeps no state between calls and never allocates or frees device memory.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Calls only enqueue work on it; they never synchronise and never copy to
+ *    the host.
+ *  - Batch is 1: a batch of B sequences is B calls.  0 <= k <= N < 2^31.
+ *  - All argument checks run on the host before the first HIP call.  On
+ *    failure nothing is enqueued, a negative status is returned and
+ *    astraea_last_error() holds a message (thread-local).
+ *  - bf16 is the upper half of IEEE binary32; conversions to bf16 round to
+ *    nearest even.
+ */
+#ifndef ASTRAEA_H
+#define ASTRAEA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { ASTRAEA_F32 = 0, ASTRAEA_BF16 = 1 } astraea_dtype;
+
+/* How the per-token change Delta is reduced over the C feature channels.
+ * The paper describes it three ways (equation text: "value difference";
+ * Algorithm 1 step 1: a mean over channels, commented as a squared
+ * difference; procedure text: absolute difference).  L2 is what the benchmark
+ * configurations use. */
+typedef enum {
+    ASTRAEA_DELTA_L2 = 0,       /* sqrt(sum_c d_c^2) */
+    ASTRAEA_DELTA_MEAN_ABS = 1, /* (sum_c |d_c|) / C */
+    ASTRAEA_DELTA_MEAN_SQ = 2   /* (sum_c d_c^2) / C */
+} astraea_delta_mode;
+
+enum {
+    ASTRAEA_OK = 0,
+    ASTRAEA_ERR_INVALID = -1,     /* NULL pointer, negative size, k > N, bad stride ... */
+    ASTRAEA_ERR_UNSUPPORTED = -2, /* dtype / head_dim combination without a kernel */
+    ASTRAEA_ERR_WORKSPACE = -3,   /* workspace missing, misaligned or too small */
+    ASTRAEA_ERR_HIP = -4          /* a HIP launch reported an error */
+};
+
+/* Operation ids for astraea_workspace_bytes. */
+enum { ASTRAEA_OP_SELECT_TOPK = 1, ASTRAEA_OP_SPARSE_ATTN = 2 };
+
+/*
+ * astraea_score - selection metric S_token (paper Sec. 3.2 "Selection Metric":
+ * S_token = w_alpha * S_sig + w_beta * S_penalty, S_sig = S_LSE,t-1 * Delta_token,t,
+ * S_penalty = e^{n_i}; Algorithm 1 steps 1-2).
+ *
+ *   x_cur, x_prev  [N, C] rows `row_stride_elems` apart, dtype `dt`: token features of
+ *                  this step and of the last computed step.
+ *   lse_weight     [N] fp32 per-token S_LSE,t-1, or NULL for weight 1.
+ *   skip_count     [N] int32 n_i (consecutive non-selections), or NULL: then the
+ *                  penalty term is left out altogether (w_beta is ignored).
+ *   penalty_table  [table_len] fp32, entry n = e^n as the caller rounded it; the
+ *                  counter is clamped to [0, table_len-1].  Required with skip_count.
+ *   score_out      [N] fp32.
+ *
+ * Arithmetic (fp32, defined to the bit so that selection is reproducible):
+ * d_c = x_cur[i,c] - x_prev[i,c]; one accumulator runs over c = 0..C-1 in order with
+ * acc = fma(d_c, d_c, acc) (or acc + |d_c|); Delta = sqrt(acc) correctly rounded, or
+ * acc / (float)C; sig = Delta * lse_weight[i]; S = w_alpha * sig, and with counters
+ * S = fma(w_beta, table[n], w_alpha * sig).
+ */
+int astraea_score(const void *x_cur, const void *x_prev, astraea_dtype dt, int64_t N, int64_t C,
+                  int64_t row_stride_elems, astraea_delta_mode mode, const float *lse_weight,
+                  const int32_t *skip_count, const float *penalty_table, int32_t table_len, float w_alpha,
+                  float w_beta, float *score_out, void *stream);
+
+/*
+ * astraea_select_topk - I_sel, I_remain = TopK(S_token, theta) (Algorithm 1 step 3).
+ * Selects the k tokens with the largest score; equal scores are won by the lower
+ * index; -0 equals +0; NaN ranks below every number.  The result is unique.
+ *
+ *   score       [N] fp32.
+ *   idx_sel     [k] int32 out, ascending token indices.
+ *   idx_remain  [N-k] int32 out, ascending, or NULL.
+ *   sel_mask    [N] uint8 out (1 = selected), or NULL.
+ *   skip_count  [N] int32 in/out, or NULL: set to 0 for selected tokens and
+ *               incremented for the others (the n_i of the penalty term).
+ *   workspace   at least astraea_workspace_bytes(ASTRAEA_OP_SELECT_TOPK, N, k, 0, 0)
+ *               bytes, 256-byte aligned; contents need not be initialised and are
+ *               clobbered.  Calls sharing a workspace must not overlap in time.
+ * k == 0 and k == N are valid.
+ */
+int astraea_select_topk(const float *score, int64_t N, int64_t k, int32_t *idx_sel, int32_t *idx_remain,
+                        uint8_t *sel_mask, int32_t *skip_count, void *workspace, size_t workspace_bytes,
+                        void *stream);
+
+/*
+ * astraea_sparse_attn_fwd - attention of the selected queries over the full-length
+ * keys and values (Algorithm 1 step 6; Sec. 3.2 "Sparse Attention"):
+ *     o_sel[r, h, :] = sum_j softmax_j(scale * <q_r,h , k_j,h>) * v_j,h      j = 0..N-1
+ * with no mask.  Row r of the result is exactly row idx_sel[r] of dense attention.
+ *
+ *   q           q_is_compact == 0: [N, H, D], the row of selected query r is
+ *               q + idx_sel[r]*q_stride_n (gathered inside the kernel);
+ *               q_is_compact == 1: [k_sel, H, D], row r is used and idx_sel may be NULL.
+ *   k, v        [N, H, D]; K/V of unselected tokens are whatever the caller cached.
+ *   strides     in elements; the head-dim index is contiguous.
+ *   o_sel       [k_sel, H, D] contiguous, dtype `dt`.
+ *   lse_sel     [k_sel, H] fp32 natural-log sum of exponentials of the scaled logits, or NULL.
+ *   workspace   at least astraea_workspace_bytes(ASTRAEA_OP_SPARSE_ATTN, ...) bytes
+ *               (may be NULL when that is 0).
+ * Supported: (BF16, D = 128) on bf16 MFMA with fp32 softmax and accumulation;
+ * (F32, D = 64 or 128) on fp32 MFMA.  k_sel == 0 enqueues nothing.
+ * Pointers must be 16-byte aligned and strides multiples of 8 elements.
+ */
+int astraea_sparse_attn_fwd(const void *q, const void *k, const void *v, astraea_dtype dt, int64_t N, int32_t H,
+                            int32_t D, int64_t q_stride_n, int64_t q_stride_h, int64_t kv_stride_n,
+                            int64_t kv_stride_h, const int32_t *idx_sel, int64_t k_sel, int q_is_compact,
+                            float softmax_scale, void *o_sel, float *lse_sel, void *workspace,
+                            size_t workspace_bytes, void *stream);
+
+/*
+ * astraea_scatter_update - cache merge (Algorithm 1 steps 6-7): rows listed in idx_sel
+ * are overwritten, every other row keeps what it held (the reuse of cached results).
+ *   src_is_full == 0: cache[idx_sel[r], :] = src[r, :]            (src is [k_sel, row_elems])
+ *   src_is_full == 1: cache[idx_sel[r], :] = src[idx_sel[r], :]   (src is [N, row_elems])
+ * The second form refreshes cached K/V rows or the stored features of the last
+ * computed step.  idx_sel must hold distinct indices in [0, N); duplicates race.
+ * Row strides are in elements.  k_sel == 0 enqueues nothing.
+ */
+int astraea_scatter_update(void *cache, const void *src, astraea_dtype dt, int64_t N, int64_t row_elems,
+                           int64_t cache_row_stride, int64_t src_row_stride, const int32_t *idx_sel,
+                           int64_t k_sel, int src_is_full, void *stream);
+
+/*
+ * astraea_gather_rows - dst[r, :] = src[idx_sel[r], :] (Algorithm 1 step 5, X_in[I_sel]).
+ */
+int astraea_gather_rows(const void *src, void *dst, astraea_dtype dt, int64_t N, int64_t row_elems,
+                        int64_t src_row_stride, int64_t dst_row_stride, const int32_t *idx_sel, int64_t k_sel,
+                        void *stream);
+
+/* Bytes of device workspace an operation needs for these sizes (host only). */
+size_t astraea_workspace_bytes(int op, int64_t N, int64_t k_sel, int32_t H, int32_t D);
+
+/* Tokens selected by a percent budget (Sec. 3.3: theta in {0, 10%, ..., 100%}):
+ * (N * pct + 50) / 100, i.e. rounded half up.  Host only. */
+int64_t astraea_budget_to_k(int64_t N, int32_t budget_percent);
+
+/* Multiply-add count of the selected-query attention, 4*k_sel*N*D*H (the QK^T and AV terms
+ * of the paper's FLOPs appendix with one N replaced by k_sel).  Host only. */
+double astraea_attn_flops(int64_t N, int64_t k_sel, int32_t H, int32_t D);
+
+const char *astraea_status_string(int status);
+const char *astraea_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ASTRAEA_H */

@@ -1,0 +1,150 @@
+"""Thin ctypes binding of libastraea: argument marshalling only.
+
+Every function has the name and the meaning of the C entry point declared in
+include/astraea.h; tensors are torch tensors living on the GPU and only their
+pointers, shapes and strides are passed on.  All arithmetic runs in the HIP
+kernels.  There is no fallback: if the library cannot be loaded, importing a
+symbol raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+from pathlib import Path
+from typing import Optional
+
+import torch
+
+_PKG = Path(__file__).resolve().parent
+LIB_PATH = _PKG / "libastraea.so"
+
+F32, BF16 = 0, 1
+DELTA_L2, DELTA_MEAN_ABS, DELTA_MEAN_SQ = 0, 1, 2
+OK, ERR_INVALID, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
+OP_SELECT_TOPK, OP_SPARSE_ATTN = 1, 2
+
+EXPORTS = (
+    "astraea_score", "astraea_select_topk", "astraea_sparse_attn_fwd", "astraea_scatter_update",
+    "astraea_gather_rows", "astraea_workspace_bytes", "astraea_budget_to_k", "astraea_attn_flops",
+    "astraea_status_string", "astraea_last_error",
+)
+
+
+class AstraeaError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"astraea status {status}: {message}")
+        self.status = status
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load libastraea.so (built in-tree by build.py); raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not LIB_PATH.exists():
+            raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_2506_05096_amd.build` "
+                              "(there is no non-HIP fallback)")
+        L = C.CDLL(str(LIB_PATH))
+        vp, i64, i32, f32, sz = C.c_void_p, C.c_int64, C.c_int32, C.c_float, C.c_size_t
+        L.astraea_score.argtypes = [vp, vp, C.c_int, i64, i64, i64, C.c_int, vp, vp, vp, i32, f32, f32, vp, vp]
+        L.astraea_select_topk.argtypes = [vp, i64, i64, vp, vp, vp, vp, vp, sz, vp]
+        L.astraea_sparse_attn_fwd.argtypes = [vp, vp, vp, C.c_int, i64, i32, i32, i64, i64, i64, i64, vp, i64,
+                                              C.c_int, f32, vp, vp, vp, sz, vp]
+        L.astraea_scatter_update.argtypes = [vp, vp, C.c_int, i64, i64, i64, i64, vp, i64, C.c_int, vp]
+        L.astraea_gather_rows.argtypes = [vp, vp, C.c_int, i64, i64, i64, i64, vp, i64, vp]
+        L.astraea_workspace_bytes.argtypes = [C.c_int, i64, i64, i32, i32]
+        L.astraea_workspace_bytes.restype = sz
+        L.astraea_budget_to_k.argtypes = [i64, i32]
+        L.astraea_budget_to_k.restype = i64
+        L.astraea_attn_flops.argtypes = [i64, i64, i32, i32]
+        L.astraea_attn_flops.restype = C.c_double
+        L.astraea_status_string.argtypes = [C.c_int]
+        L.astraea_status_string.restype = C.c_char_p
+        L.astraea_last_error.restype = C.c_char_p
+        for name in ("astraea_score", "astraea_select_topk", "astraea_sparse_attn_fwd", "astraea_scatter_update",
+                     "astraea_gather_rows"):
+            getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _check(rc: int):
+    if rc != OK:
+        raise AstraeaError(rc, lib().astraea_last_error().decode() or lib().astraea_status_string(rc).decode())
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported tensor dtype {t.dtype}")
+
+
+def _p(t: Optional[torch.Tensor]):
+    return None if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def workspace_bytes(op: int, N: int, k_sel: int = 0, H: int = 0, D: int = 0) -> int:
+    return int(lib().astraea_workspace_bytes(op, N, k_sel, H, D))
+
+
+def astraea_budget_to_k(N: int, budget_percent: int) -> int:
+    return int(lib().astraea_budget_to_k(N, budget_percent))
+
+
+def astraea_attn_flops(N: int, k_sel: int, H: int, D: int) -> float:
+    return float(lib().astraea_attn_flops(N, k_sel, H, D))
+
+
+def astraea_score(x_cur: torch.Tensor, x_prev: torch.Tensor, score_out: torch.Tensor, mode: int = DELTA_L2,
+                  lse_weight: Optional[torch.Tensor] = None, skip_count: Optional[torch.Tensor] = None,
+                  penalty_table: Optional[torch.Tensor] = None, w_alpha: float = 1.0, w_beta: float = 0.0) -> None:
+    N, Cw = x_cur.shape
+    assert x_prev.shape == x_cur.shape and x_prev.dtype == x_cur.dtype and x_cur.stride(1) == 1
+    assert x_prev.stride() == x_cur.stride() and score_out.dtype == torch.float32 and score_out.is_contiguous()
+    tl = 0 if penalty_table is None else int(penalty_table.numel())
+    _check(lib().astraea_score(_p(x_cur), _p(x_prev), _dt(x_cur), N, Cw, x_cur.stride(0), mode, _p(lse_weight),
+                               _p(skip_count), _p(penalty_table), tl, w_alpha, w_beta, _p(score_out), _stream()))
+
+
+def astraea_select_topk(score: torch.Tensor, k: int, idx_sel: torch.Tensor, workspace: torch.Tensor,
+                        idx_remain: Optional[torch.Tensor] = None, sel_mask: Optional[torch.Tensor] = None,
+                        skip_count: Optional[torch.Tensor] = None) -> None:
+    assert score.dtype == torch.float32 and score.is_contiguous() and idx_sel.dtype == torch.int32
+    _check(lib().astraea_select_topk(_p(score), score.numel(), k, _p(idx_sel), _p(idx_remain), _p(sel_mask),
+                                     _p(skip_count), _p(workspace), workspace.numel() * workspace.element_size(),
+                                     _stream()))
+
+
+def astraea_sparse_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, idx_sel: Optional[torch.Tensor],
+                            k_sel: int, o_sel: torch.Tensor, softmax_scale: float, q_is_compact: bool = False,
+                            lse_sel: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> None:
+    N, H, D = k.shape
+    assert v.shape == k.shape and v.stride() == k.stride() and q.stride(2) == 1 and k.stride(2) == 1
+    assert q.dtype == k.dtype == v.dtype == o_sel.dtype and o_sel.is_contiguous()
+    wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().astraea_sparse_attn_fwd(_p(q), _p(k), _p(v), _dt(k), N, H, D, q.stride(0), q.stride(1), k.stride(0),
+                                         k.stride(1), _p(idx_sel), k_sel, 1 if q_is_compact else 0, softmax_scale,
+                                         _p(o_sel), _p(lse_sel), _p(workspace), wsb, _stream()))
+
+
+def astraea_scatter_update(cache: torch.Tensor, src: torch.Tensor, idx_sel: torch.Tensor, k_sel: int,
+                           src_is_full: bool = False) -> None:
+    assert cache.dim() == 2 and src.dim() == 2 and cache.stride(1) == 1 and src.stride(1) == 1
+    assert cache.dtype == src.dtype and cache.shape[1] == src.shape[1]
+    _check(lib().astraea_scatter_update(_p(cache), _p(src), _dt(cache), cache.shape[0], cache.shape[1],
+                                        cache.stride(0), src.stride(0), _p(idx_sel), k_sel, 1 if src_is_full else 0,
+                                        _stream()))
+
+
+def astraea_gather_rows(src: torch.Tensor, dst: torch.Tensor, idx_sel: torch.Tensor, k_sel: int) -> None:
+    assert src.dim() == 2 and dst.dim() == 2 and src.stride(1) == 1 and dst.stride(1) == 1
+    assert src.dtype == dst.dtype and src.shape[1] == dst.shape[1]
+    _check(lib().astraea_gather_rows(_p(src), _p(dst), _dt(src), src.shape[0], src.shape[1], src.stride(0),
+                                     dst.stride(0), _p(idx_sel), k_sel, _stream()))

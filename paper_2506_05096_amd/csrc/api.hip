@@ -1,0 +1,191 @@
+// C ABI of libastraea: host-side argument validation and dispatch.  Every check happens here,
+// before the first HIP call, so a rejected call enqueues nothing.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+
+#include "common.h"
+
+namespace astraea {
+
+static thread_local char g_err[512] = "";
+
+int fail(int status, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return status;
+}
+
+int check_launch(const char *what)
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(ASTRAEA_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+    return ASTRAEA_OK;
+}
+
+static bool dtype_ok(int dt) { return dt == ASTRAEA_F32 || dt == ASTRAEA_BF16; }
+static size_t esize(int dt) { return dt == ASTRAEA_F32 ? 4 : 2; }
+static const int64_t kMaxTokens = 2147483647LL;
+
+}  // namespace astraea
+
+using namespace astraea;
+
+extern "C" {
+
+int astraea_score(const void *x_cur, const void *x_prev, astraea_dtype dt, int64_t N, int64_t C,
+                  int64_t row_stride_elems, astraea_delta_mode mode, const float *lse_weight,
+                  const int32_t *skip_count, const float *penalty_table, int32_t table_len, float w_alpha,
+                  float w_beta, float *score_out, void *stream)
+{
+    if (!dtype_ok(dt)) return fail(ASTRAEA_ERR_UNSUPPORTED, "astraea_score: unknown dtype %d", (int)dt);
+    if (mode != ASTRAEA_DELTA_L2 && mode != ASTRAEA_DELTA_MEAN_ABS && mode != ASTRAEA_DELTA_MEAN_SQ)
+        return fail(ASTRAEA_ERR_INVALID, "astraea_score: unknown delta mode %d", (int)mode);
+    if (N < 0 || N > kMaxTokens) return fail(ASTRAEA_ERR_INVALID, "astraea_score: N=%lld out of range", (long long)N);
+    if (C <= 0) return fail(ASTRAEA_ERR_INVALID, "astraea_score: C=%lld must be positive", (long long)C);
+    if (row_stride_elems < C)
+        return fail(ASTRAEA_ERR_INVALID, "astraea_score: row stride %lld < C=%lld", (long long)row_stride_elems,
+                    (long long)C);
+    if (N > 0 && (!x_cur || !x_prev || !score_out)) return fail(ASTRAEA_ERR_INVALID, "astraea_score: NULL tensor");
+    if (((uintptr_t)x_cur | (uintptr_t)x_prev) % esize(dt) != 0 || (uintptr_t)score_out % 4 != 0)
+        return fail(ASTRAEA_ERR_INVALID, "astraea_score: pointer not aligned to its element size");
+    if (skip_count && (!penalty_table || table_len <= 0))
+        return fail(ASTRAEA_ERR_INVALID, "astraea_score: skip_count needs a penalty table");
+    return launch_score(x_cur, x_prev, dt, N, C, row_stride_elems, mode, lse_weight, skip_count, penalty_table,
+                        table_len, w_alpha, w_beta, score_out, (hipStream_t)stream);
+}
+
+int astraea_select_topk(const float *score, int64_t N, int64_t k, int32_t *idx_sel, int32_t *idx_remain,
+                        uint8_t *sel_mask, int32_t *skip_count, void *workspace, size_t workspace_bytes,
+                        void *stream)
+{
+    if (N < 0 || N > kMaxTokens)
+        return fail(ASTRAEA_ERR_INVALID, "astraea_select_topk: N=%lld out of range", (long long)N);
+    if (k < 0 || k > N)
+        return fail(ASTRAEA_ERR_INVALID, "astraea_select_topk: k=%lld not in [0, N=%lld]", (long long)k, (long long)N);
+    if (N == 0) return ASTRAEA_OK;
+    if (!score) return fail(ASTRAEA_ERR_INVALID, "astraea_select_topk: NULL score");
+    if (k > 0 && !idx_sel) return fail(ASTRAEA_ERR_INVALID, "astraea_select_topk: NULL idx_sel");
+    if (((uintptr_t)score | (uintptr_t)idx_sel | (uintptr_t)idx_remain | (uintptr_t)skip_count) % 4 != 0)
+        return fail(ASTRAEA_ERR_INVALID, "astraea_select_topk: pointer not 4-byte aligned");
+    const size_t need = topk_workspace_bytes(N);
+    if (!workspace || (uintptr_t)workspace % 256 != 0 || workspace_bytes < need)
+        return fail(ASTRAEA_ERR_WORKSPACE, "astraea_select_topk: workspace must be 256-byte aligned and >= %zu bytes",
+                    need);
+    return launch_select_topk(score, N, k, idx_sel, idx_remain, sel_mask, skip_count, workspace, (hipStream_t)stream);
+}
+
+int astraea_sparse_attn_fwd(const void *q, const void *k, const void *v, astraea_dtype dt, int64_t N, int32_t H,
+                            int32_t D, int64_t q_stride_n, int64_t q_stride_h, int64_t kv_stride_n,
+                            int64_t kv_stride_h, const int32_t *idx_sel, int64_t k_sel, int q_is_compact,
+                            float softmax_scale, void *o_sel, float *lse_sel, void *workspace,
+                            size_t workspace_bytes, void *stream)
+{
+    const char *fn = "astraea_sparse_attn_fwd";
+    if (!dtype_ok(dt)) return fail(ASTRAEA_ERR_UNSUPPORTED, "%s: unknown dtype %d", fn, (int)dt);
+    if (N <= 0 || N > kMaxTokens) return fail(ASTRAEA_ERR_INVALID, "%s: N=%lld out of range", fn, (long long)N);
+    if (H <= 0 || H > 65535) return fail(ASTRAEA_ERR_INVALID, "%s: H=%d out of range", fn, (int)H);
+    if (k_sel < 0 || k_sel > kMaxTokens || (!q_is_compact && k_sel > N))
+        return fail(ASTRAEA_ERR_INVALID, "%s: k_sel=%lld out of range", fn, (long long)k_sel);
+    if (!(dt == ASTRAEA_BF16 && D == 128) && !(dt == ASTRAEA_F32 && (D == 64 || D == 128)))
+        return fail(ASTRAEA_ERR_UNSUPPORTED, "%s: no kernel for dtype %d with head_dim %d", fn, (int)dt, (int)D);
+    if (!(softmax_scale > 0.0f) || !std::isfinite(softmax_scale))
+        return fail(ASTRAEA_ERR_INVALID, "%s: softmax_scale must be positive and finite", fn);
+    if (k_sel == 0) return ASTRAEA_OK;
+    if (!q || !k || !v || !o_sel) return fail(ASTRAEA_ERR_INVALID, "%s: NULL tensor", fn);
+    if (!q_is_compact && !idx_sel) return fail(ASTRAEA_ERR_INVALID, "%s: idx_sel is required to gather queries", fn);
+    if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o_sel) % 16 != 0)
+        return fail(ASTRAEA_ERR_INVALID, "%s: q, k, v, o_sel must be 16-byte aligned", fn);
+    if (((uintptr_t)idx_sel | (uintptr_t)lse_sel) % 4 != 0)
+        return fail(ASTRAEA_ERR_INVALID, "%s: idx_sel / lse_sel must be 4-byte aligned", fn);
+    if (q_stride_h < D || kv_stride_h < D || q_stride_n < D || kv_stride_n < D)
+        return fail(ASTRAEA_ERR_INVALID, "%s: strides must be at least head_dim", fn);
+    if ((q_stride_n | q_stride_h | kv_stride_n | kv_stride_h) % 8 != 0)
+        return fail(ASTRAEA_ERR_INVALID, "%s: strides must be multiples of 8 elements", fn);
+    const size_t need = attn_workspace_bytes(N, k_sel, H, D);
+    if (need > 0 && (!workspace || (uintptr_t)workspace % 256 != 0 || workspace_bytes < need))
+        return fail(ASTRAEA_ERR_WORKSPACE, "%s: workspace must be 256-byte aligned and >= %zu bytes", fn, need);
+    if (dt == ASTRAEA_BF16)
+        return launch_attn_bf16_d128(q, k, v, N, H, q_stride_n, q_stride_h, kv_stride_n, kv_stride_h, idx_sel, k_sel,
+                                     q_is_compact, softmax_scale, o_sel, lse_sel, workspace, (hipStream_t)stream);
+    return launch_attn_f32(q, k, v, N, H, D, q_stride_n, q_stride_h, kv_stride_n, kv_stride_h, idx_sel, k_sel,
+                           q_is_compact, softmax_scale, o_sel, lse_sel, (hipStream_t)stream);
+}
+
+static int check_rows(const char *fn, const void *a, const void *b, astraea_dtype dt, int64_t N, int64_t row_elems,
+                      int64_t stride_a, int64_t stride_b, const int32_t *idx_sel, int64_t k_sel)
+{
+    if (!dtype_ok(dt)) return fail(ASTRAEA_ERR_UNSUPPORTED, "%s: unknown dtype %d", fn, (int)dt);
+    if (N < 0 || N > kMaxTokens) return fail(ASTRAEA_ERR_INVALID, "%s: N=%lld out of range", fn, (long long)N);
+    if (k_sel < 0 || k_sel > N)
+        return fail(ASTRAEA_ERR_INVALID, "%s: k_sel=%lld not in [0, N=%lld]", fn, (long long)k_sel, (long long)N);
+    if (row_elems < 0 || stride_a < row_elems || stride_b < row_elems)
+        return fail(ASTRAEA_ERR_INVALID, "%s: row strides must be at least row_elems", fn);
+    if (k_sel == 0) return ASTRAEA_OK;
+    if (!a || !b || !idx_sel) return fail(ASTRAEA_ERR_INVALID, "%s: NULL tensor", fn);
+    if (((uintptr_t)a | (uintptr_t)b) % esize(dt) != 0 || (uintptr_t)idx_sel % 4 != 0)
+        return fail(ASTRAEA_ERR_INVALID, "%s: pointer not aligned to its element size", fn);
+    return ASTRAEA_OK;
+}
+
+int astraea_scatter_update(void *cache, const void *src, astraea_dtype dt, int64_t N, int64_t row_elems,
+                           int64_t cache_row_stride, int64_t src_row_stride, const int32_t *idx_sel,
+                           int64_t k_sel, int src_is_full, void *stream)
+{
+    int rc = check_rows("astraea_scatter_update", cache, src, dt, N, row_elems, cache_row_stride, src_row_stride,
+                        idx_sel, k_sel);
+    if (rc != ASTRAEA_OK || k_sel == 0) return rc;
+    const int64_t es = (int64_t)esize(dt);
+    return launch_move_rows(cache, src, row_elems * es, cache_row_stride * es, src_row_stride * es, idx_sel, k_sel,
+                            true, src_is_full != 0, (hipStream_t)stream);
+}
+
+int astraea_gather_rows(const void *src, void *dst, astraea_dtype dt, int64_t N, int64_t row_elems,
+                        int64_t src_row_stride, int64_t dst_row_stride, const int32_t *idx_sel, int64_t k_sel,
+                        void *stream)
+{
+    int rc = check_rows("astraea_gather_rows", src, dst, dt, N, row_elems, src_row_stride, dst_row_stride, idx_sel,
+                        k_sel);
+    if (rc != ASTRAEA_OK || k_sel == 0) return rc;
+    const int64_t es = (int64_t)esize(dt);
+    return launch_move_rows(dst, src, row_elems * es, dst_row_stride * es, src_row_stride * es, idx_sel, k_sel, false,
+                            true, (hipStream_t)stream);
+}
+
+size_t astraea_workspace_bytes(int op, int64_t N, int64_t k_sel, int32_t H, int32_t D)
+{
+    if (N < 0) return 0;
+    if (op == ASTRAEA_OP_SELECT_TOPK) return topk_workspace_bytes(N);
+    if (op == ASTRAEA_OP_SPARSE_ATTN) return attn_workspace_bytes(N, k_sel, H, D);
+    return 0;
+}
+
+int64_t astraea_budget_to_k(int64_t N, int32_t budget_percent)
+{
+    if (N < 0 || budget_percent < 0 || budget_percent > 100) return -1;
+    return (N * (int64_t)budget_percent + 50) / 100;
+}
+
+double astraea_attn_flops(int64_t N, int64_t k_sel, int32_t H, int32_t D)
+{
+    return 4.0 * (double)k_sel * (double)N * (double)D * (double)H;
+}
+
+const char *astraea_status_string(int status)
+{
+    switch (status) {
+    case ASTRAEA_OK: return "ok";
+    case ASTRAEA_ERR_INVALID: return "invalid argument";
+    case ASTRAEA_ERR_UNSUPPORTED: return "unsupported dtype or head dimension";
+    case ASTRAEA_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case ASTRAEA_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+const char *astraea_last_error(void) { return g_err; }
+
+}  // extern "C"

@@ -1,0 +1,170 @@
+// astraea_sparse_attn_fwd, fp32 mode (paper, Algorithm 1 step 6: Softmax(Q_sel K^T / sqrt(d)) V over
+// all N keys for the selected queries only).
+//
+// Everything stays in fp32: QK^T and PV run on the fp32 matrix instruction
+// v_mfma_f32_32x32x2_f32, the softmax is the online (running max / running sum) form.
+// Both products are computed transposed, S^T = K Q^T and O^T = V^T P^T, so that a lane owns one
+// query column in every accumulator: row max, row sum and the rescale factor are per-lane values
+// (one exchange between lane l and lane l+32), and the S^T accumulator registers feed the second
+// product directly as its B operand.
+//
+// Workgroup = 4 waves x 32 queries; keys are swept in tiles of 32 staged in LDS.  This is the
+// accuracy-first path for small layers; the bf16 path carries the throughput.
+#include "common.h"
+
+namespace astraea {
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int kWaves = 4;
+constexpr int kBq = 32 * kWaves;   // queries per workgroup
+constexpr int kBk = 32;            // keys per tile
+
+__device__ __forceinline__ float xhalf_max(float x)
+{
+    // max of lane l and lane l^32
+    float o = __shfl_xor(x, 32);
+    return fmaxf(x, o);
+}
+__device__ __forceinline__ float xhalf_sum(float x) { return x + __shfl_xor(x, 32); }
+
+template <int D>
+__global__ __launch_bounds__(kWaves *kWave) void attn_f32_kernel(
+    const float *__restrict__ q, const float *__restrict__ k, const float *__restrict__ v, int64_t N, int32_t H,
+    int64_t q_stride_n, int64_t q_stride_h, int64_t kv_stride_n, int64_t kv_stride_h,
+    const int32_t *__restrict__ idx_sel, int64_t k_sel, int q_is_compact, float scale_log2e,
+    float *__restrict__ o_sel, float *__restrict__ lse_sel)
+{
+    constexpr int KP = D + 2;      // K tile pitch (floats): lanes (key, d-parity) hit 64 distinct banks
+    constexpr int VP = D + 8;      // V tile pitch: rows r and r+4 land 32 banks apart
+    constexpr int DB = D / 32;
+    __shared__ float k_lds[kBk * KP];
+    __shared__ float v_lds[kBk * VP];
+
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int qc = lane & 31, hf = lane >> 5;
+    const int head = blockIdx.y;
+    const int64_t r0 = (int64_t)blockIdx.x * kBq + wave * 32;
+
+    // Q operand: lane holds query column qc, head-dim elements 2s + hf
+    int64_t r = r0 + qc;
+    if (r > k_sel - 1) r = k_sel - 1;                    // ragged last tile: duplicate a valid row, never stored
+    const int64_t qrow = q_is_compact ? r : (int64_t)idx_sel[r];
+    const float *qp = q + qrow * q_stride_n + (int64_t)head * q_stride_h;
+    float qreg[D / 2];
+#pragma unroll
+    for (int s = 0; s < D / 2; ++s) qreg[s] = qp[2 * s + hf];
+
+    floatx16 oacc[DB];
+#pragma unroll
+    for (int b = 0; b < DB; ++b)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) oacc[b][i] = 0.0f;
+    float m_run = -INFINITY;   // running max of the scaled logits in log2 units
+    float l_run = 0.0f;        // this lane's share of the running sum
+
+    const float *kb = k + (int64_t)head * kv_stride_h;
+    const float *vb = v + (int64_t)head * kv_stride_h;
+    const int64_t ntiles = (N + kBk - 1) / kBk;
+    for (int64_t t = 0; t < ntiles; ++t) {
+        const int64_t key0 = t * kBk;
+        __syncthreads();
+        // stage the tile: 32 rows x D floats each for K and V, 16-byte global loads
+        for (int c = threadIdx.x; c < kBk * (D / 4); c += kWaves * kWave) {
+            const int row = c / (D / 4), c4 = c % (D / 4);
+            int64_t key = key0 + row;
+            if (key > N - 1) key = N - 1;
+            const float4 kv4 = *reinterpret_cast<const float4 *>(kb + key * kv_stride_n + c4 * 4);
+            const float4 vv4 = *reinterpret_cast<const float4 *>(vb + key * kv_stride_n + c4 * 4);
+            float *kd = k_lds + row * KP + c4 * 4;
+            kd[0] = kv4.x; kd[1] = kv4.y; kd[2] = kv4.z; kd[3] = kv4.w;
+            *reinterpret_cast<float4 *>(v_lds + row * VP + c4 * 4) = vv4;
+        }
+        __syncthreads();
+
+        // S^T[key, q] = sum_d K[key, d] Q[q, d]
+        floatx16 sacc;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sacc[i] = 0.0f;
+#pragma unroll
+        for (int s = 0; s < D / 2; ++s) {
+            const float a = k_lds[qc * KP + 2 * s + hf];      // A: row = key (lane&31), k index = hf
+            sacc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, qreg[s], sacc, 0, 0, 0);
+        }
+        // register i of sacc: key = key0 + (i/4)*8 + hf*4 + i%4, query = qc
+        float tmax = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            float sv = sacc[i] * scale_log2e;
+            const int64_t key = key0 + (i >> 2) * 8 + hf * 4 + (i & 3);
+            if (key >= N) sv = -INFINITY;
+            sacc[i] = sv;
+            tmax = fmaxf(tmax, sv);
+        }
+        tmax = xhalf_max(tmax);
+        const float m_new = fmaxf(m_run, tmax);
+        const float alpha = exp2f(m_run - m_new);          // 0 on the first tile
+        float psum = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const float p = exp2f(sacc[i] - m_new);
+            sacc[i] = p;
+            psum += p;
+        }
+        l_run = l_run * alpha + psum;
+        m_run = m_new;
+#pragma unroll
+        for (int b = 0; b < DB; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) oacc[b][i] *= alpha;
+        // O^T[d, q] += sum_key V[key, d] P^T[key, q]; MFMA i contracts keys (i/4)*8 + i%4 (+4 in the upper half)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int key = (i >> 2) * 8 + hf * 4 + (i & 3);
+#pragma unroll
+            for (int b = 0; b < DB; ++b) {
+                const float a = v_lds[key * VP + b * 32 + qc];   // A: row = d (lane&31), k index = hf
+                oacc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, sacc[i], oacc[b], 0, 0, 0);
+            }
+        }
+    }
+
+    const float l_tot = xhalf_sum(l_run);
+    const float inv = 1.0f / l_tot;
+    const int64_t rr = r0 + qc;
+    if (rr >= k_sel) return;
+    float *op = o_sel + (rr * H + head) * (int64_t)D;
+#pragma unroll
+    for (int b = 0; b < DB; ++b)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            // registers 4g..4g+3: head-dim b*32 + g*8 + hf*4 + 0..3
+            float4 o4 = make_float4(oacc[b][4 * g] * inv, oacc[b][4 * g + 1] * inv, oacc[b][4 * g + 2] * inv,
+                                    oacc[b][4 * g + 3] * inv);
+            *reinterpret_cast<float4 *>(op + b * 32 + g * 8 + hf * 4) = o4;
+        }
+    if (lse_sel && hf == 0) lse_sel[rr * H + head] = (m_run + log2f(l_tot)) * 0.69314718055994530942f;
+}
+
+}  // namespace
+
+int launch_attn_f32(const void *q, const void *k, const void *v, int64_t N, int32_t H, int32_t D, int64_t q_stride_n,
+                    int64_t q_stride_h, int64_t kv_stride_n, int64_t kv_stride_h, const int32_t *idx_sel,
+                    int64_t k_sel, int q_is_compact, float scale, void *o_sel, float *lse_sel, hipStream_t stream)
+{
+    if (k_sel == 0) return ASTRAEA_OK;
+    dim3 grid((unsigned)((k_sel + kBq - 1) / kBq), (unsigned)H), block(kWaves * kWave);
+    const float c = scale * 1.44269504088896340736f;
+    if (D == 64)
+        hipLaunchKernelGGL(attn_f32_kernel<64>, grid, block, 0, stream, (const float *)q, (const float *)k,
+                           (const float *)v, N, H, q_stride_n, q_stride_h, kv_stride_n, kv_stride_h, idx_sel, k_sel,
+                           q_is_compact, c, (float *)o_sel, lse_sel);
+    else
+        hipLaunchKernelGGL(attn_f32_kernel<128>, grid, block, 0, stream, (const float *)q, (const float *)k,
+                           (const float *)v, N, H, q_stride_n, q_stride_h, kv_stride_n, kv_stride_h, idx_sel, k_sel,
+                           q_is_compact, c, (float *)o_sel, lse_sel);
+    return check_launch("astraea_sparse_attn_fwd(f32)");
+}
+
+}  // namespace astraea

@@ -1,0 +1,41 @@
+// Internal declarations shared by the HIP translation units of libastraea (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "astraea.h"
+
+namespace astraea {
+
+constexpr int kWave = 64;
+
+// Records a message for astraea_last_error() and returns `status`.
+int fail(int status, const char *fmt, ...);
+// Checks hipGetLastError() after a launch.
+int check_launch(const char *what);
+
+// ---- launchers (each enqueues on `stream`, arguments already validated) ----
+int launch_score(const void *x_cur, const void *x_prev, astraea_dtype dt, int64_t N, int64_t C, int64_t row_stride,
+                 astraea_delta_mode mode, const float *lse_weight, const int32_t *skip_count,
+                 const float *penalty_table, int32_t table_len, float w_alpha, float w_beta, float *score_out,
+                 hipStream_t stream);
+
+size_t topk_workspace_bytes(int64_t N);
+int launch_select_topk(const float *score, int64_t N, int64_t k, int32_t *idx_sel, int32_t *idx_remain,
+                       uint8_t *sel_mask, int32_t *skip_count, void *workspace, hipStream_t stream);
+
+int launch_move_rows(void *dst, const void *src, int64_t row_bytes, int64_t dst_stride_bytes,
+                     int64_t src_stride_bytes, const int32_t *idx, int64_t k_sel, bool index_dst, bool index_src,
+                     hipStream_t stream);
+
+size_t attn_workspace_bytes(int64_t N, int64_t k_sel, int32_t H, int32_t D);
+int launch_attn_bf16_d128(const void *q, const void *k, const void *v, int64_t N, int32_t H, int64_t q_stride_n,
+                          int64_t q_stride_h, int64_t kv_stride_n, int64_t kv_stride_h, const int32_t *idx_sel,
+                          int64_t k_sel, int q_is_compact, float scale, void *o_sel, float *lse_sel, void *workspace,
+                          hipStream_t stream);
+int launch_attn_f32(const void *q, const void *k, const void *v, int64_t N, int32_t H, int32_t D, int64_t q_stride_n,
+                    int64_t q_stride_h, int64_t kv_stride_n, int64_t kv_stride_h, const int32_t *idx_sel,
+                    int64_t k_sel, int q_is_compact, float scale, void *o_sel, float *lse_sel, hipStream_t stream);
+
+}  // namespace astraea

@@ -1,0 +1,70 @@
+// Row movers behind astraea_gather_rows and astraea_scatter_update
+// (paper, Algorithm 1: X_in[I_sel] in step 5, and the cache merge of steps 6-7).
+//
+// A token row (H*D elements, 6 KiB for 24 heads x 128 x bf16) is contiguous, so the copy is fully
+// coalesced without staging: one wavefront moves one row, each lane 16 bytes per step, all of a
+// lane's loads issued before its stores.  Unselected rows are never touched, which is exactly the
+// "reuse the cached result" half of the merge.  HBM-bound: 2 * row_bytes per selected token.
+#include "common.h"
+
+namespace astraea {
+namespace {
+
+typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
+
+constexpr int kRowsPerBlock = 4;      // one wave per row
+
+template <typename V>
+__global__ __launch_bounds__(kRowsPerBlock *kWave) void move_rows_kernel(
+    char *__restrict__ dst, const char *__restrict__ src, int64_t row_bytes, int64_t dst_stride, int64_t src_stride,
+    const int32_t *__restrict__ idx, int64_t k_sel, int index_dst, int index_src)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t r = (int64_t)blockIdx.x * kRowsPerBlock + threadIdx.x / kWave;
+    if (r >= k_sel) return;
+    const int64_t tok = idx[r];
+    const V *s = reinterpret_cast<const V *>(src + (index_src ? tok : r) * src_stride);
+    V *d = reinterpret_cast<V *>(dst + (index_dst ? tok : r) * dst_stride);
+    const int64_t nvec = row_bytes / (int64_t)sizeof(V);
+    // groups of 4, then 2, then 1 vectors per lane: every group's loads are issued before its stores
+    int64_t p = lane;
+#pragma unroll 1
+    for (; p + 3 * kWave < nvec; p += 4 * kWave) {
+        const V b0 = s[p], b1 = s[p + kWave], b2 = s[p + 2 * kWave], b3 = s[p + 3 * kWave];
+        d[p] = b0;
+        d[p + kWave] = b1;
+        d[p + 2 * kWave] = b2;
+        d[p + 3 * kWave] = b3;
+    }
+    if (p + kWave < nvec) {
+        const V b0 = s[p], b1 = s[p + kWave];
+        d[p] = b0;
+        d[p + kWave] = b1;
+        p += 2 * kWave;
+    }
+    if (p < nvec) d[p] = s[p];
+}
+
+}  // namespace
+
+int launch_move_rows(void *dst, const void *src, int64_t row_bytes, int64_t dst_stride_bytes,
+                     int64_t src_stride_bytes, const int32_t *idx, int64_t k_sel, bool index_dst, bool index_src,
+                     hipStream_t stream)
+{
+    if (k_sel == 0 || row_bytes == 0) return ASTRAEA_OK;
+    dim3 grid((unsigned)((k_sel + kRowsPerBlock - 1) / kRowsPerBlock)), block(kRowsPerBlock * kWave);
+    const uintptr_t all = (uintptr_t)dst | (uintptr_t)src | (uintptr_t)row_bytes | (uintptr_t)dst_stride_bytes |
+                          (uintptr_t)src_stride_bytes;
+    if (all % 16 == 0)
+        hipLaunchKernelGGL(move_rows_kernel<uint4v>, grid, block, 0, stream, (char *)dst, (const char *)src, row_bytes,
+                           dst_stride_bytes, src_stride_bytes, idx, k_sel, (int)index_dst, (int)index_src);
+    else if (all % 4 == 0)
+        hipLaunchKernelGGL(move_rows_kernel<uint32_t>, grid, block, 0, stream, (char *)dst, (const char *)src,
+                           row_bytes, dst_stride_bytes, src_stride_bytes, idx, k_sel, (int)index_dst, (int)index_src);
+    else
+        hipLaunchKernelGGL(move_rows_kernel<uint16_t>, grid, block, 0, stream, (char *)dst, (const char *)src,
+                           row_bytes, dst_stride_bytes, src_stride_bytes, idx, k_sel, (int)index_dst, (int)index_src);
+    return check_launch("astraea row move");
+}
+
+}  // namespace astraea

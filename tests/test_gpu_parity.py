@@ -1,0 +1,254 @@
+"""GPU parity: every C-ABI entry point against the CPU oracle on the same seeded inputs.
+
+Bars: selected indices, masks, counters and moved rows bit-exact; scores bit-exact (the score
+decides integers, both sides take it in fp32 with the same channel order); attention max-abs
+<= 1e-4 in fp32 mode and relative L2 <= 1e-2 in bf16 mode.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from conftest import bf16_bits_to_f64, to_np
+from paper_2506_05096_amd import binding as ab
+from paper_2506_05096_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def _sync():
+    torch.cuda.synchronize()
+
+
+def as_f64(a: np.ndarray) -> np.ndarray:
+    return bf16_bits_to_f64(a) if a.dtype == np.uint16 else a.astype(np.float64)
+
+
+# ------------------------------------------------------------------ score --
+
+def _features(n, c, dtype, recipe, seed, stride=None):
+    g = torch.Generator().manual_seed(seed)
+    prev = torch.randn(n, c, generator=g)
+    cur = prev + 0.1 * torch.randn(n, c, generator=g) if recipe == "drift" else torch.randn(n, c, generator=g)
+    prev, cur = prev.to(dtype), cur.to(dtype)
+    if stride is not None and stride != c:
+        pp = torch.zeros(n, stride, dtype=dtype)
+        cc = torch.zeros(n, stride, dtype=dtype)
+        pp[:, :c], cc[:, :c] = prev, cur
+        return cc, pp
+    return cur, prev
+
+
+@pytest.mark.parametrize("n,c,dtype,recipe,stride", [
+    (4096, 512, torch.float32, "independent", None),      # config-0 shape
+    (3001, 3072, torch.bfloat16, "drift", None),          # config-2/3 recipe, ragged token count
+    (257, 520, torch.bfloat16, "drift", None),            # ragged last channel slab, vector path
+    (130, 100, torch.bfloat16, "independent", None),      # rows not 16-byte aligned: element path
+    (130, 100, torch.float32, "independent", 104),        # strided rows
+    (1, 64, torch.float32, "independent", None),
+    (64, 7, torch.float32, "independent", None),
+])
+@pytest.mark.parametrize("mode", [ab.DELTA_L2, ab.DELTA_MEAN_ABS, ab.DELTA_MEAN_SQ])
+def test_score_bit_exact(n, c, dtype, recipe, stride, mode):
+    cur, prev = _features(n, c, dtype, recipe, seed=n + c, stride=stride)
+    exp = oracle.score(to_np(cur)[:, :c], to_np(prev)[:, :c], mode)
+    dc, dp = cur.to(DEV), prev.to(DEV)
+    out = torch.full((n,), -1.0, device=DEV)
+    ab.astraea_score(dc[:, :c], dp[:, :c], out, mode)
+    _sync()
+    got = out.cpu().numpy()
+    assert np.array_equal(got.view(np.uint32), exp.view(np.uint32)), \
+        f"max |diff| {np.max(np.abs(got - exp))}, mismatches {(got != exp).sum()}"
+
+
+def test_score_weight_and_penalty_bit_exact():
+    n, c = 1000, 512
+    cur, prev = _features(n, c, torch.bfloat16, "drift", seed=5)
+    g = torch.Generator().manual_seed(6)
+    w = torch.rand(n, generator=g) * 40 + 1
+    cnt = torch.randint(-1, 30, (n,), generator=g, dtype=torch.int32)
+    table = torch.from_numpy(oracle.penalty_table(20))
+    exp = oracle.score(to_np(cur), to_np(prev), ab.DELTA_L2, lse_weight=w.numpy(), skip_count=cnt.numpy(),
+                       penalty_table=table.numpy(), w_alpha=0.7, w_beta=1e-3)
+    out = torch.empty(n, device=DEV)
+    ab.astraea_score(cur.to(DEV), prev.to(DEV), out, ab.DELTA_L2, lse_weight=w.to(DEV), skip_count=cnt.to(DEV),
+                     penalty_table=table.to(DEV), w_alpha=0.7, w_beta=1e-3)
+    _sync()
+    assert np.array_equal(out.cpu().numpy().view(np.uint32), exp.view(np.uint32))
+
+
+def test_score_closed_forms_on_gpu():
+    # all-ones difference: sqrt(C) exactly; cur == prev: zero
+    for c, expect in ((1024, 32.0), (4096, 64.0)):
+        prev = torch.full((70, c), 2.0, device=DEV, dtype=torch.bfloat16)
+        cur = torch.full((70, c), 3.0, device=DEV, dtype=torch.bfloat16)
+        out = torch.empty(70, device=DEV)
+        ab.astraea_score(cur, prev, out)
+        assert torch.all(out == expect)
+        ab.astraea_score(cur, cur.clone(), out)
+        assert torch.all(out == 0)
+
+
+# ------------------------------------------------------------------ top-k --
+
+def _run_topk(score_t, k, with_skip=True):
+    n = score_t.numel()
+    ws = torch.empty(ab.workspace_bytes(ab.OP_SELECT_TOPK, n), dtype=torch.uint8, device=DEV)
+    ws.random_(0, 255)                                     # the workspace needs no initialisation
+    idx = torch.full((max(k, 1),), -7, dtype=torch.int32, device=DEV)
+    rem = torch.full((max(n - k, 1),), -7, dtype=torch.int32, device=DEV)
+    mask = torch.full((n,), 9, dtype=torch.uint8, device=DEV)
+    skip0 = torch.arange(n, dtype=torch.int32) % 5
+    skip = skip0.to(DEV) if with_skip else None
+    ab.astraea_select_topk(score_t.to(DEV), k, idx, ws, idx_remain=rem, sel_mask=mask, skip_count=skip)
+    _sync()
+    return idx[:k].cpu().numpy(), rem[:n - k].cpu().numpy(), mask.cpu().numpy(), skip0.numpy(), \
+        (skip.cpu().numpy() if with_skip else None)
+
+
+@pytest.mark.parametrize("kind", ["normal", "lognormal", "tied", "narrow", "signed_tied"])
+@pytest.mark.parametrize("n", [1, 7, 2048, 2049, 5000, 118800])
+def test_topk_bit_exact(kind, n):
+    s = synth.random_scores(n, 3 + n, kind)
+    for k in sorted({0, 1, n // 3, (3 * n) // 10, n - 1, n} & set(range(0, n + 1))):
+        e_idx, e_rem, e_mask = oracle.topk(s.numpy(), k)
+        idx, rem, mask, skip0, skip = _run_topk(s, k)
+        assert np.array_equal(idx, e_idx), (kind, n, k)
+        assert np.array_equal(rem, e_rem), (kind, n, k)
+        assert np.array_equal(mask, e_mask), (kind, n, k)
+        assert np.array_equal(skip, oracle.update_skip_count(skip0, e_mask)), (kind, n, k)
+
+
+def test_topk_special_values():
+    s = torch.tensor([float("nan"), -0.0, 0.0, float("inf"), -float("inf"), 1.0, float("nan"), 0.0, -1e-45, 1e-45,
+                      3.4e38, -3.4e38])
+    for k in range(0, s.numel() + 1):
+        e_idx, e_rem, e_mask = oracle.topk(s.numpy(), k)
+        idx, rem, mask, _, _ = _run_topk(s, k, with_skip=False)
+        assert np.array_equal(idx, e_idx) and np.array_equal(rem, e_rem) and np.array_equal(mask, e_mask), k
+
+
+def test_topk_from_gpu_scores_end_to_end():
+    # config-2/3 recipe: scores crowd in a narrow band with exact ties; selection must still agree
+    n, c = 20000, 3072
+    cur, prev = _features(n, c, torch.bfloat16, "drift", seed=77)
+    sc = torch.empty(n, device=DEV)
+    ab.astraea_score(cur.to(DEV), prev.to(DEV), sc)
+    k = (n * 3) // 10
+    e_idx, _, _ = oracle.topk(oracle.score(to_np(cur), to_np(prev)), k)
+    idx, _, _, _, _ = _run_topk(sc.cpu(), k, with_skip=False)
+    assert np.array_equal(idx, e_idx)
+
+
+def test_topk_is_deterministic_across_runs():
+    s = synth.random_scores(118800, 1, "narrow")
+    a = _run_topk(s, 35640, with_skip=False)[0]
+    for _ in range(3):
+        assert np.array_equal(a, _run_topk(s, 35640, with_skip=False)[0])
+
+
+# ------------------------------------------------------- gather / scatter --
+
+@pytest.mark.parametrize("dtype,e", [(torch.bfloat16, 3072), (torch.float32, 512), (torch.bfloat16, 5),
+                                     (torch.float32, 3), (torch.bfloat16, 8200), (torch.bfloat16, 264)])
+def test_scatter_and_gather_bit_exact(dtype, e):
+    g = torch.Generator().manual_seed(e)
+    n, k = 777, 300
+    cache = torch.randn(n, e, generator=g).to(dtype)
+    src = torch.randn(k, e, generator=g).to(dtype)
+    full = torch.randn(n, e, generator=g).to(dtype)
+    idx = torch.randperm(n, generator=g)[:k].sort().values.to(torch.int32)
+    for src_t, is_full in ((src, False), (full, True)):
+        exp = to_np(cache).copy()
+        oracle.scatter(exp, to_np(src_t), idx.numpy(), src_is_full=is_full)
+        dc = cache.to(DEV).clone()
+        ab.astraea_scatter_update(dc, src_t.to(DEV), idx.to(DEV), k, src_is_full=is_full)
+        _sync()
+        assert np.array_equal(to_np(dc), exp)
+    # budget 0: nothing moves
+    dc = cache.to(DEV).clone()
+    ab.astraea_scatter_update(dc, src.to(DEV), idx.to(DEV), 0)
+    _sync()
+    assert np.array_equal(to_np(dc), to_np(cache))
+    # gather
+    dst = torch.zeros(k, e, dtype=dtype, device=DEV)
+    ab.astraea_gather_rows(full.to(DEV), dst, idx.to(DEV), k)
+    _sync()
+    assert np.array_equal(to_np(dst), oracle.gather(to_np(full), idx.numpy()))
+
+
+# -------------------------------------------------------------- attention --
+
+def _attn_case(n, h, d, k_sel, dtype, seed, bias_std=0.0):
+    g = torch.Generator().manual_seed(seed)
+    q = torch.randn(n, h, d, generator=g)
+    k = torch.randn(n, h, d, generator=g)
+    v = torch.randn(n, h, d, generator=g)
+    if bias_std:
+        k = k + bias_std * torch.randn(1, h, d, generator=g)
+    idx = torch.randperm(n, generator=g)[:k_sel].sort().values.to(torch.int32)
+    return q.to(dtype), k.to(dtype), v.to(dtype), idx
+
+
+def _run_attn(q, k, v, idx, scale, compact=False, want_lse=True):
+    n, h, d = k.shape
+    k_sel = idx.numel()
+    o = torch.full((k_sel, h, d), float("nan"), dtype=k.dtype, device=DEV)
+    lse = torch.full((k_sel, h), float("nan"), device=DEV) if want_lse else None
+    wsb = ab.workspace_bytes(ab.OP_SPARSE_ATTN, n, k_sel, h, d)
+    ws = torch.empty(max(wsb, 1), dtype=torch.uint8, device=DEV) if wsb else None
+    dq = q[idx.long()].contiguous().to(DEV) if compact else q.to(DEV)
+    ab.astraea_sparse_attn_fwd(dq, k.to(DEV), v.to(DEV), None if compact else idx.to(DEV), k_sel, o, scale,
+                               q_is_compact=compact, lse_sel=lse, workspace=ws)
+    _sync()
+    return as_f64(to_np(o)), (lse.cpu().numpy().astype(np.float64) if want_lse else None)
+
+
+@pytest.mark.parametrize("n,h,d,k_sel", [(300, 2, 64, 77), (1000, 3, 128, 333), (33, 1, 64, 33), (129, 2, 128, 1)])
+def test_attn_f32_matches_oracle(n, h, d, k_sel):
+    q, k, v, idx = _attn_case(n, h, d, k_sel, torch.float32, seed=n)
+    scale = 1.0 / math.sqrt(d)
+    eo, else_ = oracle.sparse_attn(to_np(q), to_np(k), to_np(v), idx.numpy(), scale)
+    for compact in (False, True):
+        o, lse = _run_attn(q, k, v, idx, scale, compact=compact)
+        assert np.max(np.abs(o - eo)) <= 1e-4, np.max(np.abs(o - eo))
+        assert np.max(np.abs(lse - else_)) <= 1e-4
+
+
+def _rel_l2(a, b):
+    return float(np.linalg.norm((a - b).ravel()) / np.linalg.norm(b.ravel()))
+
+
+@pytest.mark.parametrize("n,h,k_sel,bias", [(1000, 3, 333, 0.0), (64, 1, 64, 0.0), (129, 2, 1, 0.0),
+                                            (2500, 2, 130, 0.5), (4096, 2, 128, 0.0)])
+def test_attn_bf16_matches_oracle(n, h, k_sel, bias):
+    d = 128
+    q, k, v, idx = _attn_case(n, h, d, k_sel, torch.bfloat16, seed=n + 1, bias_std=bias)
+    scale = 1.0 / math.sqrt(d)
+    eo, else_ = oracle.sparse_attn(to_np(q), to_np(k), to_np(v), idx.numpy(), scale)
+    for compact in (False, True):
+        o, lse = _run_attn(q, k, v, idx, scale, compact=compact)
+        assert np.all(np.isfinite(o))
+        assert _rel_l2(o, eo) <= 1e-2, _rel_l2(o, eo)
+        assert np.max(np.abs(lse - else_)) <= 2e-2
+
+
+def test_attn_bf16_peaked_and_uniform_rows():
+    # peaked: one key dominates a row by a wide margin -> that V row; uniform: zero queries -> mean of V.
+    n, h, d = 700, 2, 128
+    g = torch.Generator().manual_seed(4)
+    v = torch.randn(n, h, d, generator=g).bfloat16()
+    k = torch.zeros(n, h, d)
+    k[123, :, 0] = 64.0
+    q = torch.zeros(n, h, d)
+    q[:, :, 0] = 16.0                        # logit 1024 * scale for key 123, 0 elsewhere
+    idx = torch.arange(0, n, 5, dtype=torch.int32)
+    o, _ = _run_attn(q.bfloat16(), k.bfloat16(), v, idx, 1.0 / math.sqrt(d))
+    assert np.array_equal(o, np.broadcast_to(as_f64(to_np(v))[123][None], o.shape))
+    o, lse = _run_attn(torch.zeros(n, h, d).bfloat16(), k.bfloat16(), v, idx, 1.0 / math.sqrt(d))
+    vm = as_f64(to_np(v)).mean(axis=0)
+    assert np.max(np.abs(o - vm[None])) < 2e-3
+    assert np.max(np.abs(lse - math.log(n))) < 1e-4
