@@ -1,0 +1,228 @@
+#!/usr/bin/env python3
+"""Benchmark of the token-wise attention hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic inputs already resident in HBM:
+score -> top-k -> refresh of the selected K/V cache rows -> attention of the selected queries over the
+full-length K/V -> scatter into the cached outputs.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3] [--budget PCT]
+    python bench.py --sweep            # config 4: per-step time against a drawn budget schedule
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from pathlib import Path
+
+ROOT = Path(__file__).resolve().parent
+if str(ROOT) not in sys.path:
+    sys.path.insert(0, str(ROOT))
+
+METRIC = "selected-token attn TFLOP/s (% MFMA peak) + ms/layer, N=118800 H=24 D=128"
+PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}     # MI355X dense MFMA peaks
+PEAK_HBM_GBS = 8000.0
+
+
+def _np(t):
+    import numpy as np
+    import torch
+    t = t.detach().cpu().contiguous()
+    return t.view(torch.int16).numpy().view(np.uint16) if t.dtype == torch.bfloat16 else t.numpy()
+
+
+def cpu_baseline(w, t, idx_sel_host, k, scale, target_s=15.0):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: score and top-k in full,
+    attention and scatter on the first `rows` selected tokens (all heads, all N keys)."""
+    import numpy as np
+    import oracle
+    n, H, D = w.N, w.H, w.D
+    xc, xp = _np(t["x_cur"]), _np(t["x_prev"])
+    kc, vc, q = _np(t["k_cache"]), _np(t["v_cache"]), _np(t["q"])
+    cache = _np(t["out_cache"]).copy()
+    t0 = time.perf_counter()
+    sc = oracle.score(xc, xp)
+    idx, _, _ = oracle.topk(sc, k)
+    t_sel = time.perf_counter() - t0
+    # calibrate on 2 rows, then size the sample for ~target_s
+    t0 = time.perf_counter()
+    oracle.sparse_attn(q, kc, vc, idx[:2], scale)
+    per_row = max((time.perf_counter() - t0) / 2, 1e-6)
+    rows = int(max(2, min(k, target_s / per_row)))
+    t0 = time.perf_counter()
+    o64, _ = oracle.sparse_attn(q, kc, vc, idx[:rows], scale)
+    o = oracle.round_to_dtype(o64.reshape(rows, H * D), oracle.BF16 if w.dtype == "bf16" else oracle.F32)
+    oracle.scatter(cache, o, idx[:rows])
+    t_attn = time.perf_counter() - t0
+    flops = 4.0 * rows * n * D * H
+    return {
+        "value": flops / (t_sel * rows / max(k, 1) + t_attn) / 1e12,
+        "unit": "TFLOP/s",
+        "cores": oracle.num_threads(),
+        "kind": "oracle",
+        "sample": f"score+top-k on all {n} tokens ({t_sel:.2f} s, charged pro rata), attention+scatter on the first "
+                  f"{rows} of {k} selected tokens x {H} heads x {n} keys ({t_attn:.2f} s, fp64 accumulation)",
+        "indices_match_gpu": bool(np.array_equal(idx, idx_sel_host)),
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="cfg3")
+    ap.add_argument("--budget", type=int, default=None, help="token budget in percent (default: the workload's)")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--sweep", action="store_true", help="config 4: 50-step budget schedule")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2506_05096_amd import binding as ab
+    from paper_2506_05096_amd import synth
+    from paper_2506_05096_amd.build import ensure_built
+    from paper_2506_05096_amd.layer import LayerStep
+
+    ensure_built()
+    ab.lib()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = synth.WORKLOADS[args.workload]
+    if args.sweep:
+        return sweep(args, w if args.workload == "cfg4" else synth.WORKLOADS["cfg4"])
+    budget = args.budget if args.budget is not None else w.budgets_pct[0]
+    t = synth.make_layer_inputs(w, seed=args.seed, device=dev)
+    layer = LayerStep(w.N, w.H, w.D, w.torch_dtype, device=dev)
+    k = layer.budget_to_k(budget)
+    es = 2 if w.dtype == "bf16" else 4
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    for _ in range(args.warmup):
+        layer.run(t, k)
+    torch.cuda.synchronize()
+    attn_ev = [(ev(), ev()) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        layer.step_score(t)
+        layer.step_select(k)
+        layer.step_kv_refresh(t, k)
+        attn_ev[s][0].record()
+        layer.step_attn(t, k)
+        attn_ev[s][1].record()
+        layer.step_scatter(t, k)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    attn_ms = sum(a.elapsed_time(b) for a, b in attn_ev) / args.steps
+
+    # untimed second pass: per-call durations for the breakdown
+    names = ["score", "select_topk", "kv_refresh", "attn", "scatter"]
+    calls = [lambda: layer.step_score(t), lambda: layer.step_select(k), lambda: layer.step_kv_refresh(t, k),
+             lambda: layer.step_attn(t, k), lambda: layer.step_scatter(t, k)]
+    reps = max(3, min(args.steps, 10))
+    br = {}
+    for nm, fn in zip(names, calls):
+        a, b = ev(), ev()
+        fn()
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        br[nm] = a.elapsed_time(b) / reps
+
+    flops = ab.astraea_attn_flops(w.N, k, w.H, w.D)
+    row_bytes = w.H * w.D * es
+    gbs = {
+        "score": (2 * w.C * es + 4) * w.N / br["score"] / 1e6,
+        "select_topk": (4 * 4 * w.N + 4 * k) / br["select_topk"] / 1e6,       # 3 radix passes + count, + indices
+        "kv_refresh": 2 * 2 * row_bytes * k / br["kv_refresh"] / 1e6,
+        "scatter": 2 * row_bytes * k / br["scatter"] / 1e6,
+    }
+    peak = PEAK_TFLOPS[w.dtype]
+    achieved = flops / attn_ms / 1e9
+    out = {
+        "metric": METRIC,
+        "value": flops / wall_ms / 1e9,
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": wall_ms,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: N={w.N} H={w.H} D={w.D} C={w.C} budget={budget}% k={k} "
+                               f"latent={'x'.join(map(str, w.latent))}",
+                   "value_definition": "4*k*N*D*H flops / ms_per_step (whole hot path)", "seed": args.seed},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+                     "frac": achieved / peak, "traffic": None,
+                     "kernel": "attn_bf16_kernel" if w.dtype == "bf16" else "attn_f32_kernel",
+                     "kernel_ms": attn_ms, "flops_per_launch": flops},
+        "breakdown_ms": br,
+        "hbm_GBps": gbs,
+        "hbm_frac_of_8TBps": {k_: v_ / PEAK_HBM_GBS for k_, v_ in gbs.items()},
+    }
+    if not args.no_cpu_baseline:
+        idx_host = layer.idx_sel[:k].cpu().numpy()
+        out["cpu_baseline"] = cpu_baseline(w, t, idx_host, k, layer.scale, args.cpu_seconds)
+    print(json.dumps(out))
+    return 0
+
+
+def sweep(args, w) -> int:
+    """Config 4: fresh tensors per step, budgets drawn from the seed; per-step ms against budget."""
+    import numpy as np
+    import torch
+    from paper_2506_05096_amd import synth
+    from paper_2506_05096_amd.layer import LayerStep
+    dev = "cuda:0"
+    sched = synth.budget_schedule(args.seed, 50)
+    layer = LayerStep(w.N, w.H, w.D, w.torch_dtype, device=dev)
+    t = synth.make_layer_inputs(w, seed=args.seed, device=dev, step=0)
+    layer.run(t, layer.budget_to_k(100))           # warm-up (also the dense reference shape)
+    torch.cuda.synchronize()
+    rows = []
+    for s, pct in enumerate(sched):
+        fresh = synth.make_layer_inputs(w, seed=args.seed, device=dev, step=s + 1)
+        for name in ("x_prev", "x_cur", "q", "k_new", "v_new"):
+            t[name] = fresh[name]                  # caches (K, V, outputs) are carried across steps
+        del fresh
+        k = layer.budget_to_k(pct)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        layer.run(t, k)
+        b.record()
+        torch.cuda.synchronize()
+        rows.append((pct, a.elapsed_time(b)))
+        print(f"step {s:2d} budget {pct:3d}% k={k:6d} {rows[-1][1]:8.3f} ms", file=sys.stderr, flush=True)
+    x = np.array([r[0] for r in rows], float)
+    y = np.array([r[1] for r in rows], float)
+    slope = float((x * y).sum() / (x * x).sum())            # least-squares line through the origin
+    dev_rel = np.abs(y - slope * x) / (slope * x)
+    dense = float(np.mean(y[x == 100])) if np.any(x == 100) else slope * 100
+    by_budget = {int(p): float(np.mean(y[x == p])) for p in sorted(set(x))}
+    print(json.dumps({
+        "metric": "config-4 budget sweep: ms per layer-step vs token budget",
+        "workload": f"cfg4: N={w.N} H={w.H} D={w.D}, 50 steps, budgets ~ U{{10..100%}}",
+        "ms_by_budget": by_budget, "ms_per_percent": slope,
+        "max_rel_dev_from_linear": float(dev_rel.max()), "mean_rel_dev_from_linear": float(dev_rel.mean()),
+        "total_ms": float(y.sum()), "dense_step_ms": dense, "total_vs_50_dense": float(y.sum() / (50 * dense)),
+        "mean_budget_pct": float(x.mean()),
+    }))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -139,6 +139,11 @@ __global__ __launch_bounds__(kWaves *kWave, 2) void attn_bf16_kernel(
     const int64_t ntiles = (N + kBk - 1) / kBk;
     issue_loads(0);
     store_tile(0);
+    // The Q fragment must be resident before the loop starts: a load still counted as pending at the
+    // loop header would make the compiler wait on the vector-memory counter inside the loop, and
+    // that wait would also drain the next tile's prefetch every iteration.
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s) asm volatile("" ::"v"(qf[s]));
     __syncthreads();
 
     for (int64_t t = 0; t < ntiles; ++t) {
