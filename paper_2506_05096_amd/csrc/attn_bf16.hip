@@ -10,14 +10,20 @@
 //    and the S^T accumulator registers, converted to bf16, are the B operand of the second
 //    product as they stand: register group 8*(t%2)..+7 of key block t/2 feeds MFMA t, with the key
 //    order inside the contraction permuted the same way on the V side.
-//  * V^T fragments come straight from a row-major [key][d] LDS tile through the transposing LDS
-//    read ds_read_b64_tr_b16, so neither K nor V is transposed in memory.
+//  * K/V tiles go from global memory straight into LDS (global_load_lds_dwordx4), double
+//    buffered, with no register staging.  Such a load writes 64 x 16 B contiguously, so rows
+//    cannot be padded; bank conflicts are avoided by an XOR swizzle of the 16-byte chunks inside
+//    each 256-byte row, applied through the per-lane global address.
+//  * V^T fragments come from the row-major [key][d] tile through the transposing LDS read
+//    ds_read_b64_tr_b16, so neither K nor V is transposed in memory.
 //  * queries are gathered by index while loading the Q fragment, which then lives in registers
 //    for the whole sweep (the "gather" step of the path is fused here).
 //  * the rescale of the O accumulators is lazy: the running max is only raised when some row's
 //    max grew by more than 2^kTau, so stale maxima cost range, not accuracy.
 //  * workgroup ids are mapped so that the workgroups resident on one XCD work on the same head and
 //    sweep the keys together; K/V tiles are then served from that XCD's L2.
+#include <type_traits>
+
 #include "common.h"
 
 namespace astraea {
@@ -26,20 +32,19 @@ namespace {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef short short4v __attribute__((ext_vector_type(4)));
-typedef short short8v __attribute__((ext_vector_type(8)));
 typedef uint32_t uint2v __attribute__((ext_vector_type(2)));
 typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
 
 constexpr int D = 128;
 constexpr int kWaves = 4;
-constexpr int kBq = 32 * kWaves;   // queries per workgroup
-constexpr int kBk = 64;            // keys per LDS tile
-constexpr int KP = D + 8;          // K tile pitch in elements (272 B): b128 row reads conflict-free
-constexpr int VP = D + 32;         // V tile pitch in elements (320 B): 4 rows x 64 B spread over all banks
-constexpr float kTau = 8.0f;       // lazy-rescale threshold, log2 units
+constexpr int kBq = 32 * kWaves;        // queries per workgroup
+constexpr int kBk = 64;                 // keys per LDS tile
+constexpr int kRowBytes = D * 2;        // 256 B per key row, unpadded
+constexpr int kTileBytes = kBk * kRowBytes;          // 16 KiB
+constexpr int kBufBytes = 2 * kTileBytes;            // K tile then V tile
+constexpr float kTau = 8.0f;            // lazy-rescale threshold, log2 units
 constexpr int kNumXcd = 8;
 
 __device__ __forceinline__ float xhalf_max(float x)
@@ -59,13 +64,31 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));   // v_cvt_pk_bf16_f32, RNE
 }
 
+__device__ __forceinline__ bf16x8 lds_read_b128(uint32_t addr)
+{
+    return *reinterpret_cast<const bf16x8 __attribute__((address_space(3))) *>((uintptr_t)addr);
+}
 // Transposing LDS read: within each group of 16 lanes, lane i receives element (i % 4) of the
 // 8-byte rows addressed by lanes 4j + i/4, j = 0..3.
-__device__ __forceinline__ short4v lds_read_tr(const __bf16 *p)
+__device__ __forceinline__ short4v lds_read_tr(uint32_t addr)
 {
-    return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-        (short4v __attribute__((address_space(3))) *)(uintptr_t)(const void *)p);
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3))) *)(uintptr_t)addr);
 }
+
+// 16 bytes per lane from global memory straight into LDS: lane l of the wave lands at
+// lds_wave_base + 16*l.  The LDS base travels in M0.  Completion is counted by vmcnt; the kernel
+// waits for it explicitly before the barrier that publishes the tile.
+__device__ __forceinline__ void dma16(const void *gbase, uint32_t goff, uint32_t lds_wave_base)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_wave_base), "v"(goff), "s"(gbase)
+                 : "memory");
+}
+__device__ __forceinline__ void wait_dma() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+constexpr int MFMA = 0x008, DSR = 0x100;
+#define SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
 
 __global__ __launch_bounds__(kWaves *kWave, 2) void attn_bf16_kernel(
     const __bf16 *__restrict__ q, const __bf16 *__restrict__ k, const __bf16 *__restrict__ v, int64_t N, int32_t H,
@@ -73,8 +96,8 @@ __global__ __launch_bounds__(kWaves *kWave, 2) void attn_bf16_kernel(
     const int32_t *__restrict__ idx_sel, int64_t k_sel, int q_is_compact, float scale_log2e,
     __bf16 *__restrict__ o_sel, float *__restrict__ lse_sel, int32_t q_tiles, int64_t items_per_xcd)
 {
-    __shared__ __attribute__((aligned(16))) __bf16 k_lds[2][kBk * KP];
-    __shared__ __attribute__((aligned(16))) __bf16 v_lds[2][kBk * VP];
+    // [buffer][K tile | V tile]; 64 KiB, two workgroups per CU
+    __shared__ __attribute__((aligned(1024))) char lds[2 * kBufBytes];
 
     // work item = (head, query tile), head-major; XCD x owns the contiguous item range
     // [x * items_per_xcd, (x+1) * items_per_xcd), and workgroups reach XCDs round-robin by id.
@@ -85,9 +108,11 @@ __global__ __launch_bounds__(kWaves *kWave, 2) void attn_bf16_kernel(
     const int head = (int)(item / q_tiles);
     const int64_t qt = item % q_tiles;
 
-    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int qc = lane & 31, hf = lane >> 5;
     const int64_t r0 = qt * kBq + wave * 32;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
 
     // ---- Q fragment: lane holds query column qc, head-dim 16*s + 8*hf + 0..7 (B operand of K Q^T)
     int64_t r = r0 + qc;
@@ -106,64 +131,93 @@ __global__ __launch_bounds__(kWaves *kWave, 2) void attn_bf16_kernel(
     float m_c = -INFINITY;     // running max of scale*log2(e)*logit actually used as exponent offset
     float l_run = 0.0f;        // this lane's share of the running sum
 
-    // ---- tile staging: thread loads 4 x 16 B of K and of V per tile
-    const __bf16 *kbase = k + (int64_t)head * kv_stride_h;
-    const __bf16 *vbase = v + (int64_t)head * kv_stride_h;
-    const int ld_row = tid >> 4, ld_c16 = tid & 15;   // + 16 rows per step
-    uint4v kst[4], vst[4];
-    auto issue_loads = [&](int64_t key0) {
+    // ---- tile DMA.  A wave instruction fills 4 consecutive rows (1 KiB) of a tile: lane l writes
+    // physical chunk l%16 of row l/16.  Wave w issues blocks w, w+4, w+8, w+12 of K and of V.
+    // Physical chunk p of row r holds logical chunk p ^ (r & 15) for K and p ^ (4 * (r & 3)) for V.
+    const char *kbase = reinterpret_cast<const char *>(k + (int64_t)head * kv_stride_h);
+    const char *vbase = reinterpret_cast<const char *>(v + (int64_t)head * kv_stride_h);
+    const int64_t row_pitch = kv_stride_n * 2;       // bytes between consecutive keys
+    const int d_row = lane >> 4, d_p = lane & 15;
+    auto issue_dma = [&](int64_t key0, int buf) {
+        const int64_t last = N - 1 - key0;           // rows past the last key re-read it (masked later)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            int64_t key = key0 + ld_row + 16 * i;
-            if (key > N - 1) key = N - 1;           // ragged last tile: valid rows, masked below
-            kst[i] = *reinterpret_cast<const uint4v *>(kbase + key * kv_stride_n + ld_c16 * 8);
-            vst[i] = *reinterpret_cast<const uint4v *>(vbase + key * kv_stride_n + ld_c16 * 8);
-        }
-    };
-    auto store_tile = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int row = ld_row + 16 * i;
-            *reinterpret_cast<uint4v *>(&k_lds[buf][row * KP + ld_c16 * 8]) = kst[i];
-            *reinterpret_cast<uint4v *>(&v_lds[buf][row * VP + ld_c16 * 8]) = vst[i];
+            const int blk = 4 * i + wave;
+            const int rr = 4 * blk + d_row;
+            const int64_t rc = rr < last ? rr : last;
+            const uint32_t ko = (uint32_t)(rc * row_pitch) + ((d_p ^ (rr & 15)) << 4);
+            const uint32_t vo = (uint32_t)(rc * row_pitch) + ((d_p ^ ((rr & 3) << 2)) << 4);
+            const uint32_t dst = lds0 + buf * kBufBytes + blk * 1024;
+            dma16(kbase + key0 * row_pitch, ko, dst);
+            dma16(vbase + key0 * row_pitch, vo, dst + kTileBytes);
         }
     };
 
-    // V^T fragment addressing for the transposing read (see lds_read_tr): lane i of a 16-lane
-    // group addresses key row (i / 4) of a 4-row band and 4 head-dim elements at 4 * (i % 4);
-    // groups 0/1 (lanes 0-31) take the band at +0, groups 2/3 the band at +4 keys;
-    // odd groups take head-dim +16.
-    const int li = lane & 15;
-    const int v_off = (4 * hf + (li >> 2)) * VP + ((lane >> 4) & 1) * 16 + 4 * (li & 3);
+    // ---- LDS read addresses (lane part; tile, buffer and block offsets are immediates)
+    // K fragment (kb, s): row 32*kb + qc, logical chunk 2*s + hf
+    uint32_t ka[D / 16];
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s) ka[s] = lds0 + qc * kRowBytes + (((2 * s + hf) ^ (qc & 15)) << 4);
+    // V^T fragment (tt, b, half): lane i of a 16-lane group addresses row 16*tt + 8*half + 4*hf + i/4,
+    // head-dim 32*b + 16*(group & 1) + 4*(i % 4) .. +3
+    const int li = lane & 15, vr = li >> 2;
+    uint32_t va[4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+        va[b] = lds0 + kTileBytes + (4 * hf + vr) * kRowBytes +
+                ((((4 * b) ^ (vr << 2)) + 2 * ((lane >> 4) & 1) + ((li & 3) >> 1)) << 4) + 8 * (li & 1);
 
     const int64_t ntiles = (N + kBk - 1) / kBk;
-    issue_loads(0);
-    store_tile(0);
+    issue_dma(0, 0);
     // The Q fragment must be resident before the loop starts: a load still counted as pending at the
-    // loop header would make the compiler wait on the vector-memory counter inside the loop, and
-    // that wait would also drain the next tile's prefetch every iteration.
+    // loop header would make the compiler wait on the vector-memory counter inside the loop.
 #pragma unroll
     for (int s = 0; s < D / 16; ++s) asm volatile("" ::"v"(qf[s]));
+    wait_dma();
     __syncthreads();
 
-    for (int64_t t = 0; t < ntiles; ++t) {
-        const int buf = (int)(t & 1);
+    auto tile_step = [&](int64_t t, auto buf_tag) {
+        constexpr int BUF = decltype(buf_tag)::value;
+        constexpr uint32_t KOFF = BUF * kBufBytes;
         const int64_t key0 = t * kBk;
-        if (t + 1 < ntiles) issue_loads(key0 + kBk);
+        if (t + 1 < ntiles) issue_dma(key0 + kBk, BUF ^ 1);
 
         // ---- S^T[key, q] = sum_d K[key, d] Q[q, d]; two blocks of 32 keys
         floatx16 sacc[2];
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) sacc[kb][i] = 0.0f;
-            const __bf16 *kp = &k_lds[buf][(32 * kb + qc) * KP + 8 * hf];
-#pragma unroll
-            for (int s = 0; s < D / 16; ++s) {
-                const bf16x8 a = *reinterpret_cast<const bf16x8 *>(kp + 16 * s);
-                sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[s], sacc[kb], 0, 0, 0);
-            }
+        for (int i = 0; i < 16; ++i) {
+            sacc[0][i] = 0.0f;
+            sacc[1][i] = 0.0f;
         }
+        bf16x8 kf[D / 16], kg[D / 16];
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) kf[s] = lds_read_b128(ka[s] + KOFF);
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) {
+            sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[s], sacc[0], 0, 0, 0);
+            kg[s] = lds_read_b128(ka[s] + KOFF + 32 * kRowBytes);
+        }
+        // V^T fragments of the first 32 keys are fetched under the second block's MFMAs
+        short4v vh[2][4][2];
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) {
+            sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kg[s], qf[s], sacc[1], 0, 0, 0);
+            const int tt = s >> 2, b = s & 3;
+            vh[tt][b][0] = lds_read_tr(va[b] + KOFF + (16 * tt) * kRowBytes);
+            vh[tt][b][1] = lds_read_tr(va[b] + KOFF + (16 * tt + 8) * kRowBytes);
+        }
+        SGB(DSR, 8);
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            SGB(MFMA, 1);
+            SGB(DSR, 1);
+        }
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            SGB(MFMA, 1);
+            SGB(DSR, 2);
+        }
+
         // register i of sacc[kb]: key = key0 + 32*kb + (i/4)*8 + hf*4 + i%4, query = qc
         if (key0 + kBk > N) {
 #pragma unroll
@@ -204,6 +258,7 @@ __global__ __launch_bounds__(kWaves *kWave, 2) void attn_bf16_kernel(
 
         // ---- O^T[d, q] += sum_key V[key, d] P^T[key, q]; MFMA tt contracts the 16 keys
         //      16*tt + {0..3, 8..11} (lanes 0-31) and 16*tt + {4..7, 12..15} (lanes 32-63)
+        short4v wh[2][4][2];
 #pragma unroll
         for (int tt = 0; tt < 4; ++tt) {
             const int kb = tt >> 1, rb = 8 * (tt & 1);
@@ -211,19 +266,34 @@ __global__ __launch_bounds__(kWaves *kWave, 2) void attn_bf16_kernel(
 #pragma unroll
             for (int j = 0; j < 4; ++j) pw[j] = pack_bf16(sacc[kb][rb + 2 * j], sacc[kb][rb + 2 * j + 1]);
             const bf16x8 pf = __builtin_bit_cast(bf16x8, pw);
-            const __bf16 *vp = &v_lds[buf][16 * tt * VP + v_off];
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
-                const short4v h0 = lds_read_tr(vp + 32 * b);
-                const short4v h1 = lds_read_tr(vp + 32 * b + 8 * VP);
+                const short4v h0 = tt < 2 ? vh[tt][b][0] : wh[tt - 2][b][0];
+                const short4v h1 = tt < 2 ? vh[tt][b][1] : wh[tt - 2][b][1];
                 const bf16x8 vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(h0, h1, 0, 1, 2, 3, 4, 5, 6, 7));
                 oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[b], 0, 0, 0);
+                if (tt < 2) {   // fetch the fragments of keys 32..63 under the first 8 MFMAs
+                    wh[tt][b][0] = lds_read_tr(va[b] + KOFF + (16 * (tt + 2)) * kRowBytes);
+                    wh[tt][b][1] = lds_read_tr(va[b] + KOFF + (16 * (tt + 2) + 8) * kRowBytes);
+                }
             }
         }
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            SGB(MFMA, 1);
+            SGB(DSR, 2);
+        }
 
-        if (t + 1 < ntiles) store_tile(buf ^ 1);
+        wait_dma();
         __syncthreads();
+    };
+
+    int64_t t = 0;
+    for (; t + 1 < ntiles; t += 2) {
+        tile_step(t, std::integral_constant<int, 0>{});
+        tile_step(t + 1, std::integral_constant<int, 1>{});
     }
+    if (t < ntiles) tile_step(t, std::integral_constant<int, 0>{});
 
     const float l_tot = xhalf_sum(l_run);
     const float inv = 1.0f / l_tot;
@@ -253,6 +323,9 @@ int launch_attn_bf16_d128(const void *q, const void *k, const void *v, int64_t N
                           hipStream_t stream)
 {
     if (k_sel == 0) return ASTRAEA_OK;
+    // a tile's lane offsets are 32-bit: 64 rows must span less than 4 GiB
+    if (kv_stride_n * 2 * kBk >= (int64_t)1 << 32)
+        return fail(ASTRAEA_ERR_UNSUPPORTED, "astraea_sparse_attn_fwd: K/V token stride too large");
     const int64_t q_tiles = (k_sel + kBq - 1) / kBq;
     const int64_t total = q_tiles * H;
     const int64_t per_xcd = (total + kNumXcd - 1) / kNumXcd;
