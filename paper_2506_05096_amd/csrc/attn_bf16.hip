@@ -38,7 +38,7 @@ typedef uint32_t uint2v __attribute__((ext_vector_type(2)));
 typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
 
 constexpr int D = 128;
-constexpr int kWaves = 4;
+constexpr int kWaves = 8;
 constexpr int kBq = 32 * kWaves;        // queries per workgroup
 constexpr int kBk = 64;                 // keys per LDS tile
 constexpr int kRowBytes = D * 2;        // 256 B per key row, unpadded
@@ -90,13 +90,13 @@ __device__ __forceinline__ void wait_dma() { asm volatile("s_waitcnt vmcnt(0)" :
 constexpr int MFMA = 0x008, DSR = 0x100;
 #define SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
 
-__global__ __launch_bounds__(kWaves *kWave, 2) void attn_bf16_kernel(
+__global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
     const __bf16 *__restrict__ q, const __bf16 *__restrict__ k, const __bf16 *__restrict__ v, int64_t N, int32_t H,
     int64_t q_stride_n, int64_t q_stride_h, int64_t kv_stride_n, int64_t kv_stride_h,
     const int32_t *__restrict__ idx_sel, int64_t k_sel, int q_is_compact, float scale_log2e,
     __bf16 *__restrict__ o_sel, float *__restrict__ lse_sel, int32_t q_tiles, int64_t items_per_xcd)
 {
-    // [buffer][K tile | V tile]; 64 KiB, two workgroups per CU
+    // [buffer][K tile | V tile]; 64 KiB, one 8-wave workgroup per CU (two waves per SIMD)
     __shared__ __attribute__((aligned(1024))) char lds[2 * kBufBytes];
 
     // work item = (head, query tile), head-major; XCD x owns the contiguous item range
@@ -132,24 +132,39 @@ __global__ __launch_bounds__(kWaves *kWave, 2) void attn_bf16_kernel(
     float l_run = 0.0f;        // this lane's share of the running sum
 
     // ---- tile DMA.  A wave instruction fills 4 consecutive rows (1 KiB) of a tile: lane l writes
-    // physical chunk l%16 of row l/16.  Wave w issues blocks w, w+4, w+8, w+12 of K and of V.
+    // physical chunk l%16 of row l/16.  Wave w issues blocks w, w + kWaves, ... of K and of V.
     // Physical chunk p of row r holds logical chunk p ^ (r & 15) for K and p ^ (4 * (r & 3)) for V.
+    constexpr int kDmaPerWave = (kBk / 4) / kWaves;
     const char *kbase = reinterpret_cast<const char *>(k + (int64_t)head * kv_stride_h);
     const char *vbase = reinterpret_cast<const char *>(v + (int64_t)head * kv_stride_h);
     const int64_t row_pitch = kv_stride_n * 2;       // bytes between consecutive keys
     const int d_row = lane >> 4, d_p = lane & 15;
-    auto issue_dma = [&](int64_t key0, int buf) {
-        const int64_t last = N - 1 - key0;           // rows past the last key re-read it (masked later)
+    uint32_t koff[kDmaPerWave], voff[kDmaPerWave];   // lane offsets inside a full tile
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int blk = 4 * i + wave;
-            const int rr = 4 * blk + d_row;
-            const int64_t rc = rr < last ? rr : last;
-            const uint32_t ko = (uint32_t)(rc * row_pitch) + ((d_p ^ (rr & 15)) << 4);
-            const uint32_t vo = (uint32_t)(rc * row_pitch) + ((d_p ^ ((rr & 3) << 2)) << 4);
-            const uint32_t dst = lds0 + buf * kBufBytes + blk * 1024;
-            dma16(kbase + key0 * row_pitch, ko, dst);
-            dma16(vbase + key0 * row_pitch, vo, dst + kTileBytes);
+    for (int i = 0; i < kDmaPerWave; ++i) {
+        const int rr = 4 * (kWaves * i + wave) + d_row;
+        koff[i] = (uint32_t)(rr * row_pitch) + ((d_p ^ (rr & 15)) << 4);
+        voff[i] = (uint32_t)(rr * row_pitch) + ((d_p ^ ((rr & 3) << 2)) << 4);
+    }
+    auto issue_dma = [&](int64_t key0, int buf) {
+        const char *kt = kbase + key0 * row_pitch, *vt = vbase + key0 * row_pitch;
+        if (key0 + kBk <= N) {
+#pragma unroll
+            for (int i = 0; i < kDmaPerWave; ++i) {
+                const uint32_t dst = lds0 + buf * kBufBytes + (kWaves * i + wave) * 1024;
+                dma16(kt, koff[i], dst);
+                dma16(vt, voff[i], dst + kTileBytes);
+            }
+        } else {
+            const int64_t last = N - 1 - key0;       // rows past the last key re-read it (masked later)
+#pragma unroll
+            for (int i = 0; i < kDmaPerWave; ++i) {
+                const int rr = 4 * (kWaves * i + wave) + d_row;
+                const int64_t rc = rr < last ? rr : last;
+                const uint32_t dst = lds0 + buf * kBufBytes + (kWaves * i + wave) * 1024;
+                dma16(kt, (uint32_t)(rc * row_pitch) + ((d_p ^ (rr & 15)) << 4), dst);
+                dma16(vt, (uint32_t)(rc * row_pitch) + ((d_p ^ ((rr & 3) << 2)) << 4), dst + kTileBytes);
+            }
         }
     };
 
