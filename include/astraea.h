@@ -111,8 +111,10 @@ int astraea_select_topk(const float *score, int64_t N, int64_t k, int32_t *idx_s
  *   strides     in elements; the head-dim index is contiguous.
  *   o_sel       [k_sel, H, D] contiguous, dtype `dt`.
  *   lse_sel     [k_sel, H] fp32 natural-log sum of exponentials of the scaled logits, or NULL.
- *   workspace   at least astraea_workspace_bytes(ASTRAEA_OP_SPARSE_ATTN, ...) bytes
- *               (may be NULL when that is 0).
+ *   workspace   at least astraea_workspace_bytes(ASTRAEA_OP_SPARSE_ATTN, N, k_sel, H, D) bytes,
+ *               256-byte aligned (may be NULL when that is 0).  The bf16 path stages a
+ *               re-tiled copy of V there (N rounded up to 64, times H*D*2 bytes) on every
+ *               call; contents need not be initialised and are clobbered.
  * Supported: (BF16, D = 128) on bf16 MFMA with fp32 softmax and accumulation;
  * (F32, D = 64 or 128) on fp32 MFMA.  k_sel == 0 enqueues nothing.
  * Pointers must be 16-byte aligned and strides multiples of 8 elements.
@@ -143,7 +145,7 @@ int astraea_gather_rows(const void *src, void *dst, astraea_dtype dt, int64_t N,
                         int64_t src_row_stride, int64_t dst_row_stride, const int32_t *idx_sel, int64_t k_sel,
                         void *stream);
 
-/* Bytes of device workspace an operation needs for these sizes (host only). */
+/* Bytes of device workspace an operation needs for these sizes, valid for either dtype (host only). */
 size_t astraea_workspace_bytes(int op, int64_t N, int64_t k_sel, int32_t H, int32_t D);
 
 /* Tokens selected by a percent budget (Sec. 3.3: theta in {0, 10%, ..., 100%}):

@@ -105,7 +105,7 @@ int astraea_sparse_attn_fwd(const void *q, const void *k, const void *v, astraea
         return fail(ASTRAEA_ERR_INVALID, "%s: strides must be at least head_dim", fn);
     if ((q_stride_n | q_stride_h | kv_stride_n | kv_stride_h) % 8 != 0)
         return fail(ASTRAEA_ERR_INVALID, "%s: strides must be multiples of 8 elements", fn);
-    const size_t need = attn_workspace_bytes(N, k_sel, H, D);
+    const size_t need = dt == ASTRAEA_BF16 ? attn_bf16_workspace_bytes(N, H) : 0;
     if (need > 0 && (!workspace || (uintptr_t)workspace % 256 != 0 || workspace_bytes < need))
         return fail(ASTRAEA_ERR_WORKSPACE, "%s: workspace must be 256-byte aligned and >= %zu bytes", fn, need);
     if (dt == ASTRAEA_BF16)
@@ -159,7 +159,8 @@ size_t astraea_workspace_bytes(int op, int64_t N, int64_t k_sel, int32_t H, int3
 {
     if (N < 0) return 0;
     if (op == ASTRAEA_OP_SELECT_TOPK) return topk_workspace_bytes(N);
-    if (op == ASTRAEA_OP_SPARSE_ATTN) return attn_workspace_bytes(N, k_sel, H, D);
+    // enough for either dtype: only the bf16 path (head_dim 128) stages anything
+    if (op == ASTRAEA_OP_SPARSE_ATTN) return D == 128 ? attn_bf16_workspace_bytes(N, H) : 0;
     return 0;
 }
 
