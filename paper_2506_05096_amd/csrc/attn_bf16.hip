@@ -14,13 +14,8 @@
 //    buffered, with no register staging.  Such a load writes 64 x 16 B contiguously, so rows
 //    cannot be padded; bank conflicts are avoided by an XOR swizzle of the 16-byte chunks inside
 //    each 256-byte row, applied through the per-lane global address.
-//  * the LDS pipe issues one wave instruction every ~4.5 clocks whatever its width, so fragments
-//    must come in 16-byte reads.  K rows are head-dim contiguous, which is what S^T = K Q^T wants.
-//    V is contracted over keys, so a pre-pass rewrites V once per call into 16 KiB tiles of V^T
-//    ([128 head-dim rows][64 keys], keys permuted inside each group of 16 to match the register
-//    order of P^T, 16-byte chunks already XOR-swizzled); the main kernel then copies a tile
-//    linearly into LDS and reads every V^T fragment with one ds_read_b128.  The pre-pass moves
-//    2*N*H*D*2 bytes, under 1% of the attention time, and needs N_pad*H*D*2 bytes of workspace.
+//  * V^T fragments come from the row-major [key][d] tile through the transposing LDS read
+//    ds_read_b64_tr_b16, so neither K nor V is transposed in memory.
 //  * queries are gathered by index while loading the Q fragment, which then lives in registers
 //    for the whole sweep (the "gather" step of the path is fused here).
 //  * the rescale of the O accumulators is lazy: the running max is only raised when some row's
@@ -73,6 +68,13 @@ __device__ __forceinline__ bf16x8 lds_read_b128(uint32_t addr)
 {
     return *reinterpret_cast<const bf16x8 __attribute__((address_space(3))) *>((uintptr_t)addr);
 }
+// Transposing LDS read: within each group of 16 lanes, lane i receives element (i % 4) of the
+// 8-byte rows addressed by lanes 4j + i/4, j = 0..3.
+__device__ __forceinline__ short4v lds_read_tr(uint32_t addr)
+{
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3))) *)(uintptr_t)addr);
+}
+
 // 16 bytes per lane from global memory straight into LDS: lane l of the wave lands at
 // lds_wave_base + 16*l.  The LDS base travels in M0.  Completion is counted by vmcnt; the kernel
 // waits for it explicitly before the barrier that publishes the tile.
@@ -85,56 +87,11 @@ __device__ __forceinline__ void dma16(const void *gbase, uint32_t goff, uint32_t
 }
 __device__ __forceinline__ void wait_dma() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
-
-// ---- pre-pass: V [N, H, 128] -> tiles of V^T.  Tile (head, T) is 16 KiB at
-// vt + (head * ntiles + T) * 16 KiB and holds keys 64*T .. 64*T+63: row d (128 bytes) = 8 chunks;
-// logical chunk c = 2*t + hf holds keys 64*T + 16*t + 8*(j/4) + 4*hf + j%4 for j = 0..7, and is
-// stored at physical chunk c ^ ((d >> 1) & 7).  Keys past N are zero.
-__global__ __launch_bounds__(256) void transpose_v_kernel(const __bf16 *__restrict__ v, int64_t N, int64_t kv_stride_n,
-                                                          int64_t kv_stride_h, int64_t ntiles,
-                                                          char *__restrict__ vt)
-{
-    __shared__ uint16_t tile[kBk][D + 2];      // [key][d], odd dword pitch: column reads conflict-free
-    const int64_t T = blockIdx.x;
-    const int head = blockIdx.y;
-    const uint16_t *vb = reinterpret_cast<const uint16_t *>(v) + (int64_t)head * kv_stride_h;
-    const int tid = threadIdx.x;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int row = (tid >> 4) + 16 * i, c16 = tid & 15;
-        const int64_t key = T * kBk + row;
-        uint4v val = {0u, 0u, 0u, 0u};
-        if (key < N) val = *reinterpret_cast<const uint4v *>(vb + key * kv_stride_n + c16 * 8);
-        uint32_t *dst = reinterpret_cast<uint32_t *>(&tile[row][c16 * 8]);
-        dst[0] = val[0];
-        dst[1] = val[1];
-        dst[2] = val[2];
-        dst[3] = val[3];
-    }
-    __syncthreads();
-    char *out = vt + ((int64_t)head * ntiles + T) * kTileBytes;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int o = tid + 256 * i;           // output chunk id: row d = o / 8, logical chunk c = o % 8
-        const int d = o >> 3, c = o & 7, t = c >> 1, hf = c & 1;
-        uint32_t w[4];
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-            const int j0 = 2 * jj, j1 = 2 * jj + 1;
-            const int k0 = 16 * t + 8 * (j0 >> 2) + 4 * hf + (j0 & 3);
-            const int k1 = 16 * t + 8 * (j1 >> 2) + 4 * hf + (j1 & 3);
-            w[jj] = (uint32_t)tile[k0][d] | ((uint32_t)tile[k1][d] << 16);
-        }
-        uint4v val = {w[0], w[1], w[2], w[3]};
-        *reinterpret_cast<uint4v *>(out + d * 128 + ((c ^ ((d >> 1) & 7)) << 4)) = val;
-    }
-}
-
 constexpr int MFMA = 0x008, DSR = 0x100;
 #define SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
 
 __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
-    const __bf16 *__restrict__ q, const __bf16 *__restrict__ k, const char *__restrict__ vt, int64_t N, int32_t H,
+    const __bf16 *__restrict__ q, const __bf16 *__restrict__ k, const __bf16 *__restrict__ v, int64_t N, int32_t H,
     int64_t q_stride_n, int64_t q_stride_h, int64_t kv_stride_n, int64_t kv_stride_h,
     const int32_t *__restrict__ idx_sel, int64_t k_sel, int q_is_compact, float scale_log2e,
     __bf16 *__restrict__ o_sel, float *__restrict__ lse_sel, int32_t q_tiles, int64_t items_per_xcd)
@@ -174,41 +131,39 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
     float m_c = -INFINITY;     // running max of scale*log2(e)*logit actually used as exponent offset
     float l_run = 0.0f;        // this lane's share of the running sum
 
-    // ---- tile DMA.  A wave instruction fills 1 KiB of a tile: lane l writes 16 bytes at 16*l.
-    // Wave w issues blocks w, w + kWaves, ... of the K tile and of the V^T tile.
-    // K: block = 4 key rows; physical chunk p of row r holds logical chunk p ^ (r & 15).
-    // V^T: the pre-pass already wrote the tile as its LDS image, so the copy is linear.
+    // ---- tile DMA.  A wave instruction fills 4 consecutive rows (1 KiB) of a tile: lane l writes
+    // physical chunk l%16 of row l/16.  Wave w issues blocks w, w + kWaves, ... of K and of V.
+    // Physical chunk p of row r holds logical chunk p ^ (r & 15) for K and p ^ (4 * (r & 3)) for V.
     constexpr int kDmaPerWave = (kBk / 4) / kWaves;
-    const int64_t ntiles = (N + kBk - 1) / kBk;
     const char *kbase = reinterpret_cast<const char *>(k + (int64_t)head * kv_stride_h);
-    const char *vtbase = vt + (int64_t)head * ntiles * kTileBytes;
+    const char *vbase = reinterpret_cast<const char *>(v + (int64_t)head * kv_stride_h);
     const int64_t row_pitch = kv_stride_n * 2;       // bytes between consecutive keys
     const int d_row = lane >> 4, d_p = lane & 15;
-    uint32_t koff[kDmaPerWave];                      // lane offsets inside a full K tile
+    uint32_t koff[kDmaPerWave], voff[kDmaPerWave];   // lane offsets inside a full tile
 #pragma unroll
     for (int i = 0; i < kDmaPerWave; ++i) {
         const int rr = 4 * (kWaves * i + wave) + d_row;
         koff[i] = (uint32_t)(rr * row_pitch) + ((d_p ^ (rr & 15)) << 4);
+        voff[i] = (uint32_t)(rr * row_pitch) + ((d_p ^ ((rr & 3) << 2)) << 4);
     }
-    const uint32_t voff = wave * 1024 + lane * 16;
-    auto issue_dma = [&](int64_t tile, int buf) {
-        const int64_t key0 = tile * kBk;
-        const char *kt = kbase + key0 * row_pitch, *vtile = vtbase + tile * kTileBytes;
-#pragma unroll
-        for (int i = 0; i < kDmaPerWave; ++i)
-            dma16(vtile + i * kWaves * 1024, voff, lds0 + buf * kBufBytes + kTileBytes + (kWaves * i + wave) * 1024);
+    auto issue_dma = [&](int64_t key0, int buf) {
+        const char *kt = kbase + key0 * row_pitch, *vt = vbase + key0 * row_pitch;
         if (key0 + kBk <= N) {
 #pragma unroll
-            for (int i = 0; i < kDmaPerWave; ++i)
-                dma16(kt, koff[i], lds0 + buf * kBufBytes + (kWaves * i + wave) * 1024);
+            for (int i = 0; i < kDmaPerWave; ++i) {
+                const uint32_t dst = lds0 + buf * kBufBytes + (kWaves * i + wave) * 1024;
+                dma16(kt, koff[i], dst);
+                dma16(vt, voff[i], dst + kTileBytes);
+            }
         } else {
             const int64_t last = N - 1 - key0;       // rows past the last key re-read it (masked later)
 #pragma unroll
             for (int i = 0; i < kDmaPerWave; ++i) {
                 const int rr = 4 * (kWaves * i + wave) + d_row;
                 const int64_t rc = rr < last ? rr : last;
-                dma16(kt, (uint32_t)(rc * row_pitch) + ((d_p ^ (rr & 15)) << 4),
-                      lds0 + buf * kBufBytes + (kWaves * i + wave) * 1024);
+                const uint32_t dst = lds0 + buf * kBufBytes + (kWaves * i + wave) * 1024;
+                dma16(kt, (uint32_t)(rc * row_pitch) + ((d_p ^ (rr & 15)) << 4), dst);
+                dma16(vt, (uint32_t)(rc * row_pitch) + ((d_p ^ ((rr & 3) << 2)) << 4), dst + kTileBytes);
             }
         }
     };
@@ -218,12 +173,16 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
     uint32_t ka[D / 16];
 #pragma unroll
     for (int s = 0; s < D / 16; ++s) ka[s] = lds0 + qc * kRowBytes + (((2 * s + hf) ^ (qc & 15)) << 4);
-    // V^T fragment (tt, b): row d = 32*b + qc (128-byte rows), logical chunk 2*tt + hf
+    // V^T fragment (tt, b, half): lane i of a 16-lane group addresses row 16*tt + 8*half + 4*hf + i/4,
+    // head-dim 32*b + 16*(group & 1) + 4*(i % 4) .. +3
+    const int li = lane & 15, vr = li >> 2;
     uint32_t va[4];
 #pragma unroll
-    for (int tt = 0; tt < 4; ++tt)
-        va[tt] = lds0 + kTileBytes + qc * 128 + (((2 * tt + hf) ^ ((qc >> 1) & 7)) << 4);
+    for (int b = 0; b < 4; ++b)
+        va[b] = lds0 + kTileBytes + (4 * hf + vr) * kRowBytes +
+                ((((4 * b) ^ (vr << 2)) + 2 * ((lane >> 4) & 1) + ((li & 3) >> 1)) << 4) + 8 * (li & 1);
 
+    const int64_t ntiles = (N + kBk - 1) / kBk;
     issue_dma(0, 0);
     // The Q fragment must be resident before the loop starts: a load still counted as pending at the
     // loop header would make the compiler wait on the vector-memory counter inside the loop.
@@ -236,7 +195,7 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
         constexpr int BUF = decltype(buf_tag)::value;
         constexpr uint32_t KOFF = BUF * kBufBytes;
         const int64_t key0 = t * kBk;
-        if (t + 1 < ntiles) issue_dma(t + 1, BUF ^ 1);
+        if (t + 1 < ntiles) issue_dma(key0 + kBk, BUF ^ 1);
 
         // ---- S^T[key, q] = sum_d K[key, d] Q[q, d]; two blocks of 32 keys
         floatx16 sacc[2];
@@ -254,17 +213,24 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
             kg[s] = lds_read_b128(ka[s] + KOFF + 32 * kRowBytes);
         }
         // V^T fragments of the first 32 keys are fetched under the second block's MFMAs
-        bf16x8 vf[4][4];
+        short4v vh[2][4][2];
 #pragma unroll
         for (int s = 0; s < D / 16; ++s) {
             sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kg[s], qf[s], sacc[1], 0, 0, 0);
-            vf[s >> 2][s & 3] = lds_read_b128(va[s >> 2] + KOFF + (s & 3) * 32 * 128);
+            const int tt = s >> 2, b = s & 3;
+            vh[tt][b][0] = lds_read_tr(va[b] + KOFF + (16 * tt) * kRowBytes);
+            vh[tt][b][1] = lds_read_tr(va[b] + KOFF + (16 * tt + 8) * kRowBytes);
         }
         SGB(DSR, 8);
 #pragma unroll
-        for (int s = 0; s < 16; ++s) {
+        for (int s = 0; s < 8; ++s) {
             SGB(MFMA, 1);
             SGB(DSR, 1);
+        }
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            SGB(MFMA, 1);
+            SGB(DSR, 2);
         }
 
         // register i of sacc[kb]: key = key0 + 32*kb + (i/4)*8 + hf*4 + i%4, query = qc
@@ -307,6 +273,7 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
 
         // ---- O^T[d, q] += sum_key V[key, d] P^T[key, q]; MFMA tt contracts the 16 keys
         //      16*tt + {0..3, 8..11} (lanes 0-31) and 16*tt + {4..7, 12..15} (lanes 32-63)
+        short4v wh[2][4][2];
 #pragma unroll
         for (int tt = 0; tt < 4; ++tt) {
             const int kb = tt >> 1, rb = 8 * (tt & 1);
@@ -316,15 +283,20 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
             const bf16x8 pf = __builtin_bit_cast(bf16x8, pw);
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
-                oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[tt][b], pf, oacc[b], 0, 0, 0);
-                // fragments of keys 32..63 are fetched under the first 8 MFMAs
-                if (tt < 2) vf[tt + 2][b] = lds_read_b128(va[tt + 2] + KOFF + b * 32 * 128);
+                const short4v h0 = tt < 2 ? vh[tt][b][0] : wh[tt - 2][b][0];
+                const short4v h1 = tt < 2 ? vh[tt][b][1] : wh[tt - 2][b][1];
+                const bf16x8 vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(h0, h1, 0, 1, 2, 3, 4, 5, 6, 7));
+                oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[b], 0, 0, 0);
+                if (tt < 2) {   // fetch the fragments of keys 32..63 under the first 8 MFMAs
+                    wh[tt][b][0] = lds_read_tr(va[b] + KOFF + (16 * (tt + 2)) * kRowBytes);
+                    wh[tt][b][1] = lds_read_tr(va[b] + KOFF + (16 * (tt + 2) + 8) * kRowBytes);
+                }
             }
         }
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
             SGB(MFMA, 1);
-            SGB(DSR, 1);
+            SGB(DSR, 2);
         }
 
         wait_dma();
@@ -358,34 +330,25 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
 
 }  // namespace
 
-// Workspace of the bf16 path: the V^T tiles written by the pre-pass.
-size_t attn_bf16_workspace_bytes(int64_t N, int32_t H)
-{
-    if (N <= 0 || H <= 0) return 0;
-    const int64_t ntiles = (N + kBk - 1) / kBk;
-    return (size_t)ntiles * (size_t)H * kTileBytes;
-}
+// The bf16 path stages nothing outside its inputs and outputs.
+size_t attn_bf16_workspace_bytes(int64_t, int32_t) { return 0; }
 
 int launch_attn_bf16_d128(const void *q, const void *k, const void *v, int64_t N, int32_t H, int64_t q_stride_n,
                           int64_t q_stride_h, int64_t kv_stride_n, int64_t kv_stride_h, const int32_t *idx_sel,
-                          int64_t k_sel, int q_is_compact, float scale, void *o_sel, float *lse_sel, void *workspace,
+                          int64_t k_sel, int q_is_compact, float scale, void *o_sel, float *lse_sel, void *,
                           hipStream_t stream)
 {
     if (k_sel == 0) return ASTRAEA_OK;
     // a tile's lane offsets are 32-bit: 64 rows must span less than 4 GiB
     if (kv_stride_n * 2 * kBk >= (int64_t)1 << 32)
         return fail(ASTRAEA_ERR_UNSUPPORTED, "astraea_sparse_attn_fwd: K/V token stride too large");
-    const int64_t ntiles = (N + kBk - 1) / kBk;
     const int64_t q_tiles = (k_sel + kBq - 1) / kBq;
     const int64_t total = q_tiles * H;
     const int64_t per_xcd = (total + kNumXcd - 1) / kNumXcd;
-    if (per_xcd * kNumXcd > 2147483647LL || ntiles > 2147483647LL)
-        return fail(ASTRAEA_ERR_INVALID, "astraea_sparse_attn_fwd: grid too large");
-    hipLaunchKernelGGL(transpose_v_kernel, dim3((unsigned)ntiles, (unsigned)H), dim3(256), 0, stream,
-                       (const __bf16 *)v, N, kv_stride_n, kv_stride_h, ntiles, (char *)workspace);
+    if (per_xcd * kNumXcd > 2147483647LL) return fail(ASTRAEA_ERR_INVALID, "astraea_sparse_attn_fwd: grid too large");
     dim3 grid((unsigned)(per_xcd * kNumXcd)), block(kWaves * kWave);
     hipLaunchKernelGGL(attn_bf16_kernel, grid, block, 0, stream, (const __bf16 *)q, (const __bf16 *)k,
-                       (const char *)workspace, N, H, q_stride_n, q_stride_h, kv_stride_n, kv_stride_h, idx_sel, k_sel,
+                       (const __bf16 *)v, N, H, q_stride_n, q_stride_h, kv_stride_n, kv_stride_h, idx_sel, k_sel,
                        q_is_compact, scale * 1.44269504088896340736f, (__bf16 *)o_sel, lse_sel, (int32_t)q_tiles,
                        per_xcd);
     return check_launch("astraea_sparse_attn_fwd(bf16)");

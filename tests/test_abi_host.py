@@ -1,0 +1,159 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before any HIP call (so nothing is enqueued)."""
+import ctypes as C
+import re
+from pathlib import Path
+
+import pytest
+
+from paper_2506_05096_amd import binding as ab
+from paper_2506_05096_amd.build import ensure_built
+
+ROOT = Path(__file__).resolve().parents[1]
+
+
+@pytest.fixture(scope="module")
+def L():
+    ensure_built()
+    return ab.lib()
+
+
+def test_library_exports_every_declared_symbol(L):
+    header = (ROOT / "include" / "astraea.h").read_text()
+    declared = set(re.findall(r"\b(astraea_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(ab.EXPORTS), declared ^ set(ab.EXPORTS)
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_status_strings(L):
+    assert L.astraea_status_string(0) == b"ok"
+    for code in (-1, -2, -3, -4):
+        assert len(L.astraea_status_string(code)) > 3
+    assert L.astraea_status_string(-99) == b"unknown status"
+
+
+def test_budget_to_k_and_flops(L):
+    assert ab.astraea_budget_to_k(118800, 30) == 35640
+    assert ab.astraea_budget_to_k(17550, 40) == 7020
+    assert ab.astraea_budget_to_k(7, 50) == 4
+    assert ab.astraea_budget_to_k(10, 0) == 0 and ab.astraea_budget_to_k(10, 100) == 10
+    assert ab.astraea_budget_to_k(10, 101) == -1 and ab.astraea_budget_to_k(-1, 10) == -1
+    # 4*k*N*D*H: the QK^T and AV terms of the paper's FLOPs appendix with one N replaced by k
+    assert ab.astraea_attn_flops(118800, 35640, 24, 128) == 4.0 * 35640 * 118800 * 128 * 24
+    # ratio to dense attention is the budget, as in the paper's FLOPs tables
+    assert ab.astraea_attn_flops(1000, 400, 8, 64) / ab.astraea_attn_flops(1000, 1000, 8, 64) == 0.4
+
+
+def test_workspace_sizes(L):
+    w = ab.workspace_bytes(ab.OP_SELECT_TOPK, 118800)
+    assert w % 256 == 0 and 8 * 1024 < w < 64 * 1024           # O(N / 2048) counters + a fixed histogram
+    assert ab.workspace_bytes(ab.OP_SELECT_TOPK, 1) >= 8 * 1024
+    assert ab.workspace_bytes(99, 1000) == 0
+    # attention keeps no N x N (or any other) staging buffer
+    assert ab.workspace_bytes(ab.OP_SPARSE_ATTN, 118800, 35640, 24, 128) == 0
+
+
+FAKE = 0x10000   # a non-NULL, 256-byte aligned address; rejected calls must never touch it
+
+
+def _err(L):
+    return L.astraea_last_error().decode()
+
+
+def test_score_rejects_bad_arguments(L):
+    f = L.astraea_score
+    assert f(FAKE, FAKE, 7, 10, 8, 8, 0, None, None, None, 0, 1.0, 0.0, FAKE, None) == ab.ERR_UNSUPPORTED
+    assert f(FAKE, FAKE, ab.F32, 10, 8, 8, 5, None, None, None, 0, 1.0, 0.0, FAKE, None) == ab.ERR_INVALID
+    assert f(FAKE, FAKE, ab.F32, -1, 8, 8, 0, None, None, None, 0, 1.0, 0.0, FAKE, None) == ab.ERR_INVALID
+    assert f(FAKE, FAKE, ab.F32, 10, 0, 8, 0, None, None, None, 0, 1.0, 0.0, FAKE, None) == ab.ERR_INVALID
+    assert f(FAKE, FAKE, ab.F32, 10, 8, 4, 0, None, None, None, 0, 1.0, 0.0, FAKE, None) == ab.ERR_INVALID
+    assert "stride" in _err(L)
+    assert f(None, FAKE, ab.F32, 10, 8, 8, 0, None, None, None, 0, 1.0, 0.0, FAKE, None) == ab.ERR_INVALID
+    assert f(FAKE + 2, FAKE, ab.F32, 10, 8, 8, 0, None, None, None, 0, 1.0, 0.0, FAKE, None) == ab.ERR_INVALID
+    # counters without a penalty table
+    assert f(FAKE, FAKE, ab.F32, 10, 8, 8, 0, None, FAKE, None, 0, 1.0, 0.5, FAKE, None) == ab.ERR_INVALID
+    # N == 0 is a valid no-op
+    assert f(None, None, ab.F32, 0, 8, 8, 0, None, None, None, 0, 1.0, 0.0, None, None) == ab.OK
+
+
+def test_select_topk_rejects_bad_arguments(L):
+    f = L.astraea_select_topk
+    big = 1 << 20
+    assert f(FAKE, 10, 11, FAKE, None, None, None, FAKE, big, None) == ab.ERR_INVALID
+    assert "k=11" in _err(L)
+    assert f(FAKE, 10, -1, FAKE, None, None, None, FAKE, big, None) == ab.ERR_INVALID
+    assert f(FAKE, -5, 0, FAKE, None, None, None, FAKE, big, None) == ab.ERR_INVALID
+    assert f(None, 10, 3, FAKE, None, None, None, FAKE, big, None) == ab.ERR_INVALID
+    assert f(FAKE, 10, 3, None, None, None, None, FAKE, big, None) == ab.ERR_INVALID
+    assert f(FAKE, 10, 3, FAKE, None, None, None, None, big, None) == ab.ERR_WORKSPACE
+    assert f(FAKE, 10, 3, FAKE, None, None, None, FAKE, 16, None) == ab.ERR_WORKSPACE
+    assert f(FAKE, 10, 3, FAKE, None, None, None, FAKE + 8, big, None) == ab.ERR_WORKSPACE
+    assert f(None, 0, 0, None, None, None, None, None, 0, None) == ab.OK
+
+
+def test_sparse_attn_rejects_bad_arguments(L):
+    f = L.astraea_sparse_attn_fwd
+
+    def call(dt=ab.BF16, N=100, H=2, D=128, qsn=256, qsh=128, ksn=256, ksh=128, idx=FAKE, k_sel=10, compact=0,
+             scale=0.1, q=FAKE, k=FAKE, v=FAKE, o=FAKE):
+        return f(q, k, v, dt, N, H, D, qsn, qsh, ksn, ksh, idx, k_sel, compact, scale, o, None, None, 0, None)
+
+    assert call(dt=3) == ab.ERR_UNSUPPORTED
+    assert call(D=64) == ab.ERR_UNSUPPORTED                     # bf16 path is head_dim 128 only
+    assert call(dt=ab.F32, D=96) == ab.ERR_UNSUPPORTED
+    assert call(N=0) == ab.ERR_INVALID
+    assert call(H=0) == ab.ERR_INVALID
+    assert call(k_sel=101) == ab.ERR_INVALID                    # more selected queries than tokens
+    assert call(k_sel=-1) == ab.ERR_INVALID
+    assert call(scale=0.0) == ab.ERR_INVALID and call(scale=-1.0) == ab.ERR_INVALID
+    assert call(scale=float("nan")) == ab.ERR_INVALID and call(scale=float("inf")) == ab.ERR_INVALID
+    assert call(q=None) == ab.ERR_INVALID
+    assert call(idx=None) == ab.ERR_INVALID                     # gathering needs the index list
+    assert call(q=FAKE + 8) == ab.ERR_INVALID                   # 16-byte alignment
+    assert call(ksn=100) == ab.ERR_INVALID and call(ksn=260) == ab.ERR_INVALID
+    assert call(k_sel=0, q=None, k=None, v=None, o=None, idx=None) == ab.OK     # budget 0: nothing to do
+
+
+def test_row_movers_reject_bad_arguments(L):
+    sc, ga = L.astraea_scatter_update, L.astraea_gather_rows
+    assert sc(FAKE, FAKE, 5, 10, 8, 8, 8, FAKE, 3, 0, None) == ab.ERR_UNSUPPORTED
+    assert sc(FAKE, FAKE, ab.BF16, 10, 8, 8, 8, FAKE, 11, 0, None) == ab.ERR_INVALID
+    assert sc(FAKE, FAKE, ab.BF16, 10, 8, 4, 8, FAKE, 3, 0, None) == ab.ERR_INVALID
+    assert sc(None, FAKE, ab.BF16, 10, 8, 8, 8, FAKE, 3, 0, None) == ab.ERR_INVALID
+    assert sc(FAKE, FAKE, ab.BF16, 10, 8, 8, 8, None, 3, 0, None) == ab.ERR_INVALID
+    assert sc(FAKE + 1, FAKE, ab.BF16, 10, 8, 8, 8, FAKE, 3, 0, None) == ab.ERR_INVALID
+    assert sc(None, None, ab.BF16, 10, 8, 8, 8, None, 0, 0, None) == ab.OK      # budget 0: cache untouched
+    assert ga(FAKE, FAKE, ab.F32, 10, 8, 8, 8, FAKE, 11, None) == ab.ERR_INVALID
+    assert ga(FAKE, None, ab.F32, 10, 8, 8, 8, FAKE, 3, None) == ab.ERR_INVALID
+    assert ga(None, None, ab.F32, 10, 8, 8, 8, None, 0, None) == ab.OK
+
+
+def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(ab, "_lib", None)
+    monkeypatch.setattr(ab, "LIB_PATH", tmp_path / "missing.so")
+    with pytest.raises(ImportError):
+        ab.lib()
+
+
+def test_product_path_does_not_import_the_oracle():
+    pkg = ROOT / "paper_2506_05096_amd"
+    for f in list(pkg.glob("*.py")) + list((pkg / "csrc").glob("*")):
+        text = f.read_text()
+        assert "import oracle" not in text and "from oracle" not in text and "liboracle" not in text, f
+
+
+def test_synthetic_workloads_have_the_configured_shapes():
+    from paper_2506_05096_amd import synth
+    w = synth.WORKLOADS
+    assert (w["cfg0"].N, w["cfg0"].H, w["cfg0"].D, w["cfg0"].C, w["cfg0"].dtype) == (4096, 8, 64, 512, "f32")
+    assert (w["cfg1"].N, w["cfg1"].H, w["cfg1"].D, w["cfg1"].budgets_pct) == (16384, 24, 128, (25, 50, 75))
+    assert w["cfg2"].N == 13 * 30 * 45 and w["cfg3"].N == 33 * 45 * 80 == 118800
+    for c in w.values():
+        assert c.N == c.latent[0] * c.latent[1] * c.latent[2]
+    sched = synth.budget_schedule(0, 50)
+    assert len(sched) == 50 and set(sched) <= set(range(10, 101, 10)) and sched == synth.budget_schedule(0, 50)
+    t = synth.make_layer_inputs(w["cfg2"], seed=0, N=128)
+    assert t["q"].shape == (128, 24, 128) and t["x_cur"].shape == (128, 3072) and t["out_cache"].shape == (128, 3072)
+    t2 = synth.make_layer_inputs(w["cfg2"], seed=0, N=128)
+    assert all((t[k].view(-1) == t2[k].view(-1)).all() for k in t)
