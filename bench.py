@@ -24,6 +24,9 @@ if str(ROOT) not in sys.path:
 METRIC = "selected-token attn TFLOP/s (% MFMA peak) + ms/layer, N=118800 H=24 D=128"
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}     # MI355X dense MFMA peaks
 PEAK_HBM_GBS = 8000.0
+# HBM bytes one launch of the dominant kernel moves, from rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by
+# what the same counter reads for the library's plain 1 GiB copy (profiles/hot_path_cfg3_hbm_traffic.txt).
+MEASURED_TRAFFIC_BYTES = {("cfg3", 30): 8.01e9 + 0.219e9}
 
 
 def _np(t):
@@ -68,6 +71,38 @@ def cpu_baseline(w, t, idx_sel_host, k, scale, target_s=15.0):
     }
 
 
+def measured_peaks(torch, ab, copy_reps=2):
+    """What this chip sustains on the two resources the path leans on, measured with the library's probes:
+    a register-resident bf16 MFMA loop (constant and pseudo-random operands; random data runs into the
+    power limit) and a plain 1 GiB device copy."""
+    dev = "cuda:0"
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    out = {}
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    sink = torch.empty(cus * 2 * 256, device=dev)
+    for name, rnd in (("mfma_bf16_const_TFLOPs", False), ("mfma_bf16_random_TFLOPs", True)):
+        ab.astraea_probe_mfma_bf16(cus * 2, 20000, rnd, sink)
+        a, b = ev(), ev()
+        a.record()
+        fl = ab.astraea_probe_mfma_bf16(cus * 2, 400000, rnd, sink)      # ~50 ms: long enough for clocks to settle
+        b.record()
+        torch.cuda.synchronize()
+        out[name] = fl / a.elapsed_time(b) / 1e9
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device=dev).fill_(1)
+    dst = torch.empty(n, dtype=torch.uint8, device=dev)
+    ab.astraea_probe_copy(src, dst)
+    a, b = ev(), ev()
+    a.record()
+    for _ in range(copy_reps):
+        ab.astraea_probe_copy(src, dst)
+    b.record()
+    torch.cuda.synchronize()
+    out["copy_read_plus_write_GBps"] = 2.0 * n * copy_reps / a.elapsed_time(b) / 1e6
+    out["copy_bytes_each_way"] = n
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -79,6 +114,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--sweep", action="store_true", help="config 4: 50-step budget schedule")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="only run the measurement aids: 1 GiB plain copy (x3) and the MFMA loop")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1",
@@ -97,6 +134,9 @@ def main() -> int:
     dev = "cuda:0"
     torch.cuda.set_device(0)
     w = synth.WORKLOADS[args.workload]
+    if args.calibrate:
+        print(json.dumps(measured_peaks(torch, ab, copy_reps=3)))
+        return 0
     if args.sweep:
         return sweep(args, w if args.workload == "cfg4" else synth.WORKLOADS["cfg4"])
     budget = args.budget if args.budget is not None else w.budgets_pct[0]
@@ -166,13 +206,15 @@ def main() -> int:
                                f"latent={'x'.join(map(str, w.latent))}",
                    "value_definition": "4*k*N*D*H flops / ms_per_step (whole hot path)", "seed": args.seed},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                     "frac": achieved / peak, "traffic": None,
+                     "frac": achieved / peak, "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, budget)),
+                     "traffic_unit": "bytes per launch (algorithmic: (2k+2N)*H*D*2 = %.3g)" % ((2 * k + 2 * w.N) * row_bytes),
                      "kernel": "attn_bf16_kernel" if w.dtype == "bf16" else "attn_f32_kernel",
                      "kernel_ms": attn_ms, "flops_per_launch": flops},
         "breakdown_ms": br,
         "hbm_GBps": gbs,
         "hbm_frac_of_8TBps": {k_: v_ / PEAK_HBM_GBS for k_, v_ in gbs.items()},
     }
+    out["measured_peaks"] = measured_peaks(torch, ab)
     if not args.no_cpu_baseline:
         idx_host = layer.idx_sel[:k].cpu().numpy()
         out["cpu_baseline"] = cpu_baseline(w, t, idx_host, k, layer.scale, args.cpu_seconds)

@@ -155,6 +155,22 @@ int64_t astraea_budget_to_k(int64_t N, int32_t budget_percent);
  * of the paper's FLOPs appendix with one N replaced by k_sel).  Host only. */
 double astraea_attn_flops(int64_t N, int64_t k_sel, int32_t H, int32_t D);
 
+/*
+ * Measurement aids for the benchmark; neither is a step of the method.
+ *
+ * astraea_probe_mfma_bf16 runs a register-resident loop of v_mfma_f32_32x32x16_bf16
+ * (`workgroups` workgroups of 4 waves, `iters` iterations of 4 independent MFMAs per wave) with
+ * constant or pseudo-random operands and writes one float per thread to `sink` (device,
+ * >= workgroups*256 floats).  *flops_out (host, may be NULL) receives the flops enqueued.
+ *
+ * astraea_probe_copy copies `bytes` (multiple of 16) from src to dst (device) with a plain
+ * 16-byte-per-lane kernel: a transfer of known size against which the profiler's memory
+ * counters are scaled.
+ */
+int astraea_probe_mfma_bf16(int32_t workgroups, int32_t iters, int32_t randomize, float *sink, int64_t sink_elems,
+                            double *flops_out, void *stream);
+int astraea_probe_copy(const void *src, void *dst, int64_t bytes, void *stream);
+
 const char *astraea_status_string(int status);
 const char *astraea_last_error(void);
 

@@ -25,6 +25,7 @@ OP_SELECT_TOPK, OP_SPARSE_ATTN = 1, 2
 EXPORTS = (
     "astraea_score", "astraea_select_topk", "astraea_sparse_attn_fwd", "astraea_scatter_update",
     "astraea_gather_rows", "astraea_workspace_bytes", "astraea_budget_to_k", "astraea_attn_flops",
+    "astraea_probe_mfma_bf16", "astraea_probe_copy",
     "astraea_status_string", "astraea_last_error",
 )
 
@@ -62,6 +63,10 @@ def lib() -> C.CDLL:
         L.astraea_status_string.argtypes = [C.c_int]
         L.astraea_status_string.restype = C.c_char_p
         L.astraea_last_error.restype = C.c_char_p
+        L.astraea_probe_mfma_bf16.argtypes = [i32, i32, i32, vp, i64, C.POINTER(C.c_double), vp]
+        L.astraea_probe_copy.argtypes = [vp, vp, i64, vp]
+        L.astraea_probe_mfma_bf16.restype = C.c_int
+        L.astraea_probe_copy.restype = C.c_int
         for name in ("astraea_score", "astraea_select_topk", "astraea_sparse_attn_fwd", "astraea_scatter_update",
                      "astraea_gather_rows"):
             getattr(L, name).restype = C.c_int
@@ -148,3 +153,17 @@ def astraea_gather_rows(src: torch.Tensor, dst: torch.Tensor, idx_sel: torch.Ten
     assert src.dtype == dst.dtype and src.shape[1] == dst.shape[1]
     _check(lib().astraea_gather_rows(_p(src), _p(dst), _dt(src), src.shape[0], src.shape[1], src.stride(0),
                                      dst.stride(0), _p(idx_sel), k_sel, _stream()))
+
+
+def astraea_probe_mfma_bf16(workgroups: int, iters: int, randomize: bool, sink: torch.Tensor) -> float:
+    """Enqueues the MFMA loop; returns the flops it performs."""
+    fl = C.c_double(0.0)
+    _check(lib().astraea_probe_mfma_bf16(workgroups, iters, 1 if randomize else 0, _p(sink), sink.numel(),
+                                         C.byref(fl), _stream()))
+    return fl.value
+
+
+def astraea_probe_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes
+    _check(lib().astraea_probe_copy(_p(src), _p(dst), nbytes, _stream()))

@@ -1,0 +1,85 @@
+// Measurement aids (not steps of the method): a register-resident bf16 MFMA loop that shows what the
+// matrix pipe sustains on this chip, and a plain copy kernel of known size used to calibrate the
+// memory-traffic counters of the profiler.
+#include "common.h"
+
+namespace astraea {
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ uint32_t mix(uint32_t x)
+{
+    x ^= x >> 16; x *= 0x7feb352dU; x ^= x >> 15; x *= 0x846ca68bU; x ^= x >> 16;
+    return x;
+}
+
+// 4 independent accumulator chains of v_mfma_f32_32x32x16_bf16 per wave, operands held in registers.
+// With random operands the chip runs into its power limit and lowers the clock; with constant
+// operands it does not, so both are reported.
+__global__ __launch_bounds__(256) void mfma_loop_kernel(float *sink, int iters, int randomize)
+{
+    bf16x8 a[4], b[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t h = mix(threadIdx.x * 131u + blockIdx.x * 7919u + k * 17u + j);
+            a[k][j] = (__bf16)(randomize ? ((h & 0xffff) / 32768.0f - 1.0f) : 1.0f);
+            b[k][j] = (__bf16)(randomize ? (((h >> 16) & 0xffff) / 32768.0f - 1.0f) : 1.0f);
+        }
+    floatx16 c0, c1, c2, c3;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) c0[i] = c1[i] = c2[i] = c3[i] = 0.0f;
+    for (int it = 0; it < iters; ++it) {
+        c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], b[0], c0, 0, 0, 0);
+        c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1], b[1], c1, 0, 0, 0);
+        c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2], b[2], c2, 0, 0, 0);
+        c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[3], b[3], c3, 0, 0, 0);
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += c0[i] + c1[i] + c2[i] + c3[i];
+    sink[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+__global__ __launch_bounds__(256) void copy_kernel(const uint4v *__restrict__ src, uint4v *__restrict__ dst, size_t n)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) dst[i] = src[i];
+}
+
+}  // namespace
+}  // namespace astraea
+
+using namespace astraea;
+
+extern "C" {
+
+int astraea_probe_mfma_bf16(int32_t workgroups, int32_t iters, int32_t randomize, float *sink, int64_t sink_elems,
+                            double *flops_out, void *stream)
+{
+    if (workgroups <= 0 || iters <= 0 || !sink || sink_elems < (int64_t)workgroups * 256)
+        return fail(ASTRAEA_ERR_INVALID, "astraea_probe_mfma_bf16: sink must hold workgroups*256 floats");
+    hipLaunchKernelGGL(mfma_loop_kernel, dim3((unsigned)workgroups), dim3(256), 0, (hipStream_t)stream, sink, iters,
+                       randomize);
+    // 4 waves per workgroup, 4 MFMAs per iteration, 2*32*32*16 flops each
+    if (flops_out) *flops_out = (double)workgroups * 4.0 * (double)iters * 4.0 * 32768.0;
+    return check_launch("astraea_probe_mfma_bf16");
+}
+
+int astraea_probe_copy(const void *src, void *dst, int64_t bytes, void *stream)
+{
+    if (bytes < 0 || bytes % 16 != 0 || ((uintptr_t)src | (uintptr_t)dst) % 16 != 0)
+        return fail(ASTRAEA_ERR_INVALID, "astraea_probe_copy: pointers and size must be multiples of 16 bytes");
+    if (bytes == 0) return ASTRAEA_OK;
+    if (!src || !dst) return fail(ASTRAEA_ERR_INVALID, "astraea_probe_copy: NULL pointer");
+    hipLaunchKernelGGL(copy_kernel, dim3(4096), dim3(256), 0, (hipStream_t)stream, (const uint4v *)src, (uint4v *)dst,
+                       (size_t)(bytes / 16));
+    return check_launch("astraea_probe_copy");
+}
+
+}  // extern "C"
