@@ -14,14 +14,21 @@
 //    buffered, with no register staging.  Such a load writes 64 x 16 B contiguously, so rows
 //    cannot be padded; bank conflicts are avoided by an XOR swizzle of the 16-byte chunks inside
 //    each 256-byte row, applied through the per-lane global address.
-//  * V^T fragments come from the row-major [key][d] tile through the transposing LDS read
-//    ds_read_b64_tr_b16, so neither K nor V is transposed in memory.
+//  * the LDS pipe issues one wave instruction every ~4.5 clocks whatever its width, so fragments
+//    must come in 16-byte reads.  K rows are head-dim contiguous, which is what S^T = K Q^T wants.
+//    V is contracted over keys, so a pre-pass rewrites V once per call into 16 KiB tiles of V^T
+//    ([128 head-dim rows][64 keys], keys permuted inside each group of 16 to match the register
+//    order of P^T, 16-byte chunks already XOR-swizzled); the main kernel then copies a tile
+//    linearly into LDS and reads every V^T fragment with one ds_read_b128.  The pre-pass moves
+//    2*N*H*D*2 bytes, under 1% of the attention time, and needs N_pad*H*D*2 bytes of workspace.
 //  * queries are gathered by index while loading the Q fragment, which then lives in registers
 //    for the whole sweep (the "gather" step of the path is fused here).
 //  * the rescale of the O accumulators is lazy: the running max is only raised when some row's
 //    max grew by more than 2^kTau, so stale maxima cost range, not accuracy.
 //  * workgroup ids are mapped so that the workgroups resident on one XCD work on the same head and
 //    sweep the keys together; K/V tiles are then served from that XCD's L2.
+//  * the two waves that share a SIMD alternate: while one runs the MFMAs of a tile the other runs
+//    the exponentials of its own tile, so the matrix pipe and the VALU work at the same time.
 #include <type_traits>
 
 #include "common.h"
@@ -68,13 +75,6 @@ __device__ __forceinline__ bf16x8 lds_read_b128(uint32_t addr)
 {
     return *reinterpret_cast<const bf16x8 __attribute__((address_space(3))) *>((uintptr_t)addr);
 }
-// Transposing LDS read: within each group of 16 lanes, lane i receives element (i % 4) of the
-// 8-byte rows addressed by lanes 4j + i/4, j = 0..3.
-__device__ __forceinline__ short4v lds_read_tr(uint32_t addr)
-{
-    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3))) *)(uintptr_t)addr);
-}
-
 // 16 bytes per lane from global memory straight into LDS: lane l of the wave lands at
 // lds_wave_base + 16*l.  The LDS base travels in M0.  Completion is counted by vmcnt; the kernel
 // waits for it explicitly before the barrier that publishes the tile.
@@ -87,16 +87,69 @@ __device__ __forceinline__ void dma16(const void *gbase, uint32_t goff, uint32_t
 }
 __device__ __forceinline__ void wait_dma() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
+
+// ---- pre-pass: V [N, H, 128] -> tiles of V^T.  Tile (head, T) is 16 KiB at
+// vt + (head * ntiles + T) * 16 KiB and holds keys 64*T .. 64*T+63: row d (128 bytes) = 8 chunks;
+// logical chunk c = 2*t + hf holds keys 64*T + 16*t + 8*(j/4) + 4*hf + j%4 for j = 0..7, and is
+// stored at physical chunk c ^ ((d >> 1) & 7).  Keys past N are zero.
+__global__ __launch_bounds__(256) void transpose_v_kernel(const __bf16 *__restrict__ v, int64_t N, int64_t kv_stride_n,
+                                                          int64_t kv_stride_h, int64_t ntiles,
+                                                          char *__restrict__ vt)
+{
+    __shared__ uint16_t tile[kBk][D + 2];      // [key][d], odd dword pitch: column reads conflict-free
+    const int64_t T = blockIdx.x;
+    const int head = blockIdx.y;
+    const uint16_t *vb = reinterpret_cast<const uint16_t *>(v) + (int64_t)head * kv_stride_h;
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int row = (tid >> 4) + 16 * i, c16 = tid & 15;
+        const int64_t key = T * kBk + row;
+        uint4v val = {0u, 0u, 0u, 0u};
+        if (key < N) val = *reinterpret_cast<const uint4v *>(vb + key * kv_stride_n + c16 * 8);
+        uint32_t *dst = reinterpret_cast<uint32_t *>(&tile[row][c16 * 8]);
+        dst[0] = val[0];
+        dst[1] = val[1];
+        dst[2] = val[2];
+        dst[3] = val[3];
+    }
+    __syncthreads();
+    char *out = vt + ((int64_t)head * ntiles + T) * kTileBytes;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int o = tid + 256 * i;           // output chunk id: row d = o / 8, logical chunk c = o % 8
+        const int d = o >> 3, c = o & 7, t = c >> 1, hf = c & 1;
+        uint32_t w[4];
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const int j0 = 2 * jj, j1 = 2 * jj + 1;
+            const int k0 = 16 * t + 8 * (j0 >> 2) + 4 * hf + (j0 & 3);
+            const int k1 = 16 * t + 8 * (j1 >> 2) + 4 * hf + (j1 & 3);
+            w[jj] = (uint32_t)tile[k0][d] | ((uint32_t)tile[k1][d] << 16);
+        }
+        uint4v val = {w[0], w[1], w[2], w[3]};
+        *reinterpret_cast<uint4v *>(out + d * 128 + ((c ^ ((d >> 1) & 7)) << 4)) = val;
+    }
+}
+
 constexpr int MFMA = 0x008, DSR = 0x100;
 #define SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
+// Nothing may be moved across a phase boundary: left alone, the scheduler pulls the exponentials next to
+// the MFMAs that consume them, i.e. into the other phase.
+#define PHASE_BARRIER()                    \
+    do {                                   \
+        __builtin_amdgcn_sched_barrier(0); \
+        __builtin_amdgcn_s_barrier();      \
+        __builtin_amdgcn_sched_barrier(0); \
+    } while (0)
 
 __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
-    const __bf16 *__restrict__ q, const __bf16 *__restrict__ k, const __bf16 *__restrict__ v, int64_t N, int32_t H,
+    const __bf16 *__restrict__ q, const __bf16 *__restrict__ k, const char *__restrict__ vt, int64_t N, int32_t H,
     int64_t q_stride_n, int64_t q_stride_h, int64_t kv_stride_n, int64_t kv_stride_h,
     const int32_t *__restrict__ idx_sel, int64_t k_sel, int q_is_compact, float scale_log2e,
     __bf16 *__restrict__ o_sel, float *__restrict__ lse_sel, int32_t q_tiles, int64_t items_per_xcd)
 {
-    // [buffer][K tile | V tile]; 64 KiB, one 8-wave workgroup per CU (two waves per SIMD)
+    // [parity][K tile | V^T tile]; 64 KiB, one 8-wave workgroup per CU (two waves per SIMD)
     __shared__ __attribute__((aligned(1024))) char lds[2 * kBufBytes];
 
     // work item = (head, query tile), head-major; XCD x owns the contiguous item range
@@ -131,125 +184,80 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
     float m_c = -INFINITY;     // running max of scale*log2(e)*logit actually used as exponent offset
     float l_run = 0.0f;        // this lane's share of the running sum
 
-    // ---- tile DMA.  A wave instruction fills 4 consecutive rows (1 KiB) of a tile: lane l writes
-    // physical chunk l%16 of row l/16.  Wave w issues blocks w, w + kWaves, ... of K and of V.
-    // Physical chunk p of row r holds logical chunk p ^ (r & 15) for K and p ^ (4 * (r & 3)) for V.
-    constexpr int kDmaPerWave = (kBk / 4) / kWaves;
+    // ---- tile DMA.  A wave instruction fills 1 KiB of a tile: lane l writes 16 bytes at 16*l.
+    // K: block = 4 key rows; physical chunk p of row r holds logical chunk p ^ (r & 15).
+    // V^T: the pre-pass already wrote the tile as its LDS image, so the copy is linear.
+    const int64_t ntiles = (N + kBk - 1) / kBk;
     const char *kbase = reinterpret_cast<const char *>(k + (int64_t)head * kv_stride_h);
-    const char *vbase = reinterpret_cast<const char *>(v + (int64_t)head * kv_stride_h);
+    const char *vtbase = vt + (int64_t)head * ntiles * kTileBytes;
     const int64_t row_pitch = kv_stride_n * 2;       // bytes between consecutive keys
     const int d_row = lane >> 4, d_p = lane & 15;
-    uint32_t koff[kDmaPerWave], voff[kDmaPerWave];   // lane offsets inside a full tile
+    const uint32_t lin_off = lane * 16;
+    // Copies one tile with NW waves taking part (this wave is number w of them): block b of the
+    // tile is copied by wave b % NW.
+    auto dma_v_tile = [&](int64_t tile, int par, int w, auto nw_tag) __attribute__((always_inline)) {
+        constexpr int NW = decltype(nw_tag)::value;
+        const char *src = vtbase + tile * kTileBytes + w * 1024;
+        const uint32_t dst = lds0 + par * kBufBytes + kTileBytes + w * 1024;
 #pragma unroll
-    for (int i = 0; i < kDmaPerWave; ++i) {
-        const int rr = 4 * (kWaves * i + wave) + d_row;
-        koff[i] = (uint32_t)(rr * row_pitch) + ((d_p ^ (rr & 15)) << 4);
-        voff[i] = (uint32_t)(rr * row_pitch) + ((d_p ^ ((rr & 3) << 2)) << 4);
-    }
-    auto issue_dma = [&](int64_t key0, int buf) {
-        const char *kt = kbase + key0 * row_pitch, *vt = vbase + key0 * row_pitch;
+        for (int i = 0; i < 16 / NW; ++i) dma16(src + i * NW * 1024, lin_off, dst + i * NW * 1024);
+    };
+    auto dma_k_tile = [&](int64_t tile, int par, int w, auto nw_tag) __attribute__((always_inline)) {
+        constexpr int NW = decltype(nw_tag)::value;  // 4 or 8: a wave's rows advance by 16 or 32 per step,
+        const int64_t key0 = tile * kBk;             // so row & 15 (the swizzle) is the same for all of them
+        const char *src = kbase + key0 * row_pitch;
+        const uint32_t dst = lds0 + par * kBufBytes + w * 1024;
+        const int row0 = 4 * w + d_row;
+        const uint32_t sw = (uint32_t)((d_p ^ (row0 & 15)) << 4);
         if (key0 + kBk <= N) {
+            const uint32_t off = (uint32_t)row0 * (uint32_t)row_pitch + sw;
 #pragma unroll
-            for (int i = 0; i < kDmaPerWave; ++i) {
-                const uint32_t dst = lds0 + buf * kBufBytes + (kWaves * i + wave) * 1024;
-                dma16(kt, koff[i], dst);
-                dma16(vt, voff[i], dst + kTileBytes);
-            }
+            for (int i = 0; i < 16 / NW; ++i) dma16(src + i * 4 * NW * row_pitch, off, dst + i * NW * 1024);
         } else {
             const int64_t last = N - 1 - key0;       // rows past the last key re-read it (masked later)
 #pragma unroll
-            for (int i = 0; i < kDmaPerWave; ++i) {
-                const int rr = 4 * (kWaves * i + wave) + d_row;
+            for (int i = 0; i < 16 / NW; ++i) {
+                const int rr = row0 + 4 * NW * i;
                 const int64_t rc = rr < last ? rr : last;
-                const uint32_t dst = lds0 + buf * kBufBytes + (kWaves * i + wave) * 1024;
-                dma16(kt, (uint32_t)(rc * row_pitch) + ((d_p ^ (rr & 15)) << 4), dst);
-                dma16(vt, (uint32_t)(rc * row_pitch) + ((d_p ^ ((rr & 3) << 2)) << 4), dst + kTileBytes);
+                dma16(src, (uint32_t)(rc * row_pitch) + sw, dst + i * NW * 1024);
             }
         }
     };
 
-    // ---- LDS read addresses (lane part; tile, buffer and block offsets are immediates)
-    // K fragment (kb, s): row 32*kb + qc, logical chunk 2*s + hf
+    // ---- LDS read addresses of the current parity (the parity bit is flipped in place every tile)
+    // K fragment (kb, s): row 32*kb + qc, logical chunk 2*s + hf; kb is an immediate offset
     uint32_t ka[D / 16];
 #pragma unroll
     for (int s = 0; s < D / 16; ++s) ka[s] = lds0 + qc * kRowBytes + (((2 * s + hf) ^ (qc & 15)) << 4);
-    // V^T fragment (tt, b, half): lane i of a 16-lane group addresses row 16*tt + 8*half + 4*hf + i/4,
-    // head-dim 32*b + 16*(group & 1) + 4*(i % 4) .. +3
-    const int li = lane & 15, vr = li >> 2;
+    // V^T fragment (tt, b): row d = 32*b + qc (128-byte rows), logical chunk 2*tt + hf; b is an immediate
     uint32_t va[4];
 #pragma unroll
-    for (int b = 0; b < 4; ++b)
-        va[b] = lds0 + kTileBytes + (4 * hf + vr) * kRowBytes +
-                ((((4 * b) ^ (vr << 2)) + 2 * ((lane >> 4) & 1) + ((li & 3) >> 1)) << 4) + 8 * (li & 1);
+    for (int tt = 0; tt < 4; ++tt)
+        va[tt] = lds0 + kTileBytes + qc * 128 + (((2 * tt + hf) ^ ((qc >> 1) & 7)) << 4);
 
-    const int64_t ntiles = (N + kBk - 1) / kBk;
-    issue_dma(0, 0);
-    // The Q fragment must be resident before the loop starts: a load still counted as pending at the
-    // loop header would make the compiler wait on the vector-memory counter inside the loop.
-#pragma unroll
-    for (int s = 0; s < D / 16; ++s) asm volatile("" ::"v"(qf[s]));
-    wait_dma();
-    __syncthreads();
+    floatx16 sacc[2];          // S^T of the current tile (two blocks of 32 keys)
+    uint32_t pw[16];           // P^T as bf16 pairs: pw[8*kb + i] = registers 2i, 2i+1 of block kb
 
-    auto tile_step = [&](int64_t t, auto buf_tag) {
-        constexpr int BUF = decltype(buf_tag)::value;
-        constexpr uint32_t KOFF = BUF * kBufBytes;
-        const int64_t key0 = t * kBk;
-        if (t + 1 < ntiles) issue_dma(key0 + kBk, BUF ^ 1);
-
-        // ---- S^T[key, q] = sum_d K[key, d] Q[q, d]; two blocks of 32 keys
-        floatx16 sacc[2];
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            sacc[0][i] = 0.0f;
-            sacc[1][i] = 0.0f;
-        }
-        bf16x8 kf[D / 16], kg[D / 16];
-#pragma unroll
-        for (int s = 0; s < D / 16; ++s) kf[s] = lds_read_b128(ka[s] + KOFF);
-#pragma unroll
-        for (int s = 0; s < D / 16; ++s) {
-            sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[s], sacc[0], 0, 0, 0);
-            kg[s] = lds_read_b128(ka[s] + KOFF + 32 * kRowBytes);
-        }
-        // V^T fragments of the first 32 keys are fetched under the second block's MFMAs
-        short4v vh[2][4][2];
-#pragma unroll
-        for (int s = 0; s < D / 16; ++s) {
-            sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kg[s], qf[s], sacc[1], 0, 0, 0);
-            const int tt = s >> 2, b = s & 3;
-            vh[tt][b][0] = lds_read_tr(va[b] + KOFF + (16 * tt) * kRowBytes);
-            vh[tt][b][1] = lds_read_tr(va[b] + KOFF + (16 * tt + 8) * kRowBytes);
-        }
-        SGB(DSR, 8);
-#pragma unroll
-        for (int s = 0; s < 8; ++s) {
-            SGB(MFMA, 1);
-            SGB(DSR, 1);
-        }
-#pragma unroll
-        for (int s = 0; s < 8; ++s) {
-            SGB(MFMA, 1);
-            SGB(DSR, 2);
-        }
-
-        // register i of sacc[kb]: key = key0 + 32*kb + (i/4)*8 + hf*4 + i%4, query = qc
-        if (key0 + kBk > N) {
+    // VALU phase for tile j: row max, exponentials -> pw, row sums.  The running max is only raised
+    // (and what was accumulated under the old one rescaled) when some row's max moved up by more
+    // than 2^kTau; otherwise the stale max stays in use.
+    // register i of sacc[kb]: key = 64*j + 32*kb + (i/4)*8 + hf*4 + i%4, query = qc
+    auto softmax_tile = [&](int64_t j) __attribute__((always_inline)) {
+        if ((j + 1) * kBk > N) {                    // only the last tile can be ragged
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    const int64_t key = key0 + 32 * kb + (i >> 2) * 8 + hf * 4 + (i & 3);
-                    if (key >= N) sacc[kb][i] = -INFINITY;
+                    const int key = (int)(j * kBk - N) + 32 * kb + (i >> 2) * 8 + hf * 4 + (i & 3);
+                    if (key >= 0) sacc[kb][i] = -INFINITY;
                 }
         }
-        float tmax = sacc[0][0];
+        float tm = sacc[0][0];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, sacc[kb][i]);
-        tmax = xhalf_max(tmax) * scale_log2e;
-        // lazy rescale: only when some row's max moved up by more than 2^kTau
+            for (int i = 0; i < 16; ++i) tm = fmaxf(tm, sacc[kb][i]);
+        const float tmax = xhalf_max(tm) * scale_log2e;
         if (__builtin_amdgcn_ballot_w64(tmax > m_c + kTau) != 0) {
             const float m_new = fmaxf(m_c, tmax);
             const float alpha = __builtin_amdgcn_exp2f(m_c - m_new);   // 0 on the first tile
@@ -260,55 +268,127 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
 #pragma unroll
                 for (int i = 0; i < 16; ++i) oacc[b][i] *= alpha;
         }
-        float psum = 0.0f;
+        float ps0 = 0.0f, ps1 = 0.0f;
+        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][i], scale_log2e, -m_c));
-                sacc[kb][i] = p;
-                psum += p;
-            }
-        l_run += psum;
-
-        // ---- O^T[d, q] += sum_key V[key, d] P^T[key, q]; MFMA tt contracts the 16 keys
-        //      16*tt + {0..3, 8..11} (lanes 0-31) and 16*tt + {4..7, 12..15} (lanes 32-63)
-        short4v wh[2][4][2];
-#pragma unroll
-        for (int tt = 0; tt < 4; ++tt) {
-            const int kb = tt >> 1, rb = 8 * (tt & 1);
-            uint4v pw;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) pw[j] = pack_bf16(sacc[kb][rb + 2 * j], sacc[kb][rb + 2 * j + 1]);
-            const bf16x8 pf = __builtin_bit_cast(bf16x8, pw);
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                const short4v h0 = tt < 2 ? vh[tt][b][0] : wh[tt - 2][b][0];
-                const short4v h1 = tt < 2 ? vh[tt][b][1] : wh[tt - 2][b][1];
-                const bf16x8 vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(h0, h1, 0, 1, 2, 3, 4, 5, 6, 7));
-                oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[b], 0, 0, 0);
-                if (tt < 2) {   // fetch the fragments of keys 32..63 under the first 8 MFMAs
-                    wh[tt][b][0] = lds_read_tr(va[b] + KOFF + (16 * (tt + 2)) * kRowBytes);
-                    wh[tt][b][1] = lds_read_tr(va[b] + KOFF + (16 * (tt + 2) + 8) * kRowBytes);
-                }
-            }
+        for (int u = 0; u < 16; ++u) {
+            const int kb = u >> 3, i = 2 * (u & 7);
+            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][i], scale_log2e, -m_c));
+            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][i + 1], scale_log2e, -m_c));
+            pw[u] = pack_bf16(p0, p1);
+            // the row sum adds the rounded values, the same ones the second product uses
+            if (u & 1)
+                ps1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pw[u]), ones, ps1, false);
+            else
+                ps0 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pw[u]), ones, ps0, false);
         }
-#pragma unroll
-        for (int s = 0; s < 8; ++s) {
-            SGB(MFMA, 1);
-            SGB(DSR, 2);
-        }
-
-        wait_dma();
-        __syncthreads();
+        l_run += ps0 + ps1;
     };
 
-    int64_t t = 0;
-    for (; t + 1 < ntiles; t += 2) {
-        tile_step(t, std::integral_constant<int, 0>{});
-        tile_step(t + 1, std::integral_constant<int, 1>{});
+    constexpr int kAhead = 4;      // an MFMA's fragment is fetched kAhead MFMAs before it issues
+    // O^T += V^T(j) P^T(j): 16 MFMAs; group tt contracts the 16 keys 16*tt + {0..3, 8..11} (lanes 0-31)
+    // and 16*tt + {4..7, 12..15} (lanes 32-63).  V^T(j) is in the parity va[] points at.
+    auto pv_mfmas = [&]() __attribute__((always_inline)) {
+        bf16x8 vf[16];
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) vf[u] = lds_read_b128(va[u >> 2] + (u & 3) * 32 * 128);
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int tt = u >> 2, b = u & 3;
+            uint4v p4 = {pw[4 * tt], pw[4 * tt + 1], pw[4 * tt + 2], pw[4 * tt + 3]};
+            oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[u], __builtin_bit_cast(bf16x8, p4), oacc[b], 0, 0, 0);
+            if (u + kAhead < 16) vf[u + kAhead] = lds_read_b128(va[(u + kAhead) >> 2] + ((u + kAhead) & 3) * 32 * 128);
+        }
+        SGB(DSR, kAhead);
+#pragma unroll
+        for (int u = 0; u < 16 - kAhead; ++u) {
+            SGB(MFMA, 1);
+            SGB(DSR, 1);
+        }
+        SGB(MFMA, kAhead);
+    };
+    // S^T = K Q^T for the tile in the parity ka[] points at: 16 MFMAs, two blocks of 32 keys
+    auto qk_mfmas = [&]() __attribute__((always_inline)) {
+        bf16x8 kf[16];
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) kf[u] = lds_read_b128(ka[u & 7] + (u >> 3) * 32 * kRowBytes);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            sacc[0][i] = 0.0f;
+            sacc[1][i] = 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            sacc[u >> 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[u], qf[u & 7], sacc[u >> 3], 0, 0, 0);
+            if (u + kAhead < 16)
+                kf[u + kAhead] = lds_read_b128(ka[(u + kAhead) & 7] + ((u + kAhead) >> 3) * 32 * kRowBytes);
+        }
+        SGB(DSR, kAhead);
+#pragma unroll
+        for (int u = 0; u < 16 - kAhead; ++u) {
+            SGB(MFMA, 1);
+            SGB(DSR, 1);
+        }
+        SGB(MFMA, kAhead);
+    };
+    auto flip_k = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) ka[s] ^= kBufBytes;
+    };
+    auto flip_v = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) va[tt] ^= kBufBytes;
+    };
+
+    // ---- ping-pong schedule.  K tile j lives in K buffer j & 1, V^T tile j in V buffer j & 1.
+    // The 8 waves form two groups of 4 (one wave of each group per SIMD).  Each wave alternates a VALU
+    // phase (exponentials of tile j) and an MFMA phase (second product of tile j, first product of
+    // tile j+1), with a workgroup barrier after every phase.  Group 1 runs one phase behind group 0,
+    // so on every SIMD one wave is in its MFMA phase while the other is in its VALU phase.  Group 1
+    // also streams the tiles: during its VALU phase for tile j the buffers of V^T(j+1) and K(j+2) are
+    // free (both groups are past the MFMA phase that read them), and the copies are waited for at the
+    // end of its following MFMA phase, one phase before group 0 needs them.  Every wave executes the
+    // same number of barriers: group 1 one more at the start, group 0 one more at the end.
+    const int grp = wave >> 2, wig = wave & 3;
+    using W4 = std::integral_constant<int, 4>;
+    using W8 = std::integral_constant<int, 8>;
+    dma_k_tile(0, 0, wave, W8{});
+    dma_v_tile(0, 0, wave, W8{});
+    if (ntiles > 1) dma_k_tile(1, 1, wave, W8{});
+    // The Q fragment must be resident before the loop starts: a load still counted as pending at the
+    // loop header would make the compiler wait on the vector-memory counter inside the loop.
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s) asm volatile("" ::"v"(qf[s]));
+    wait_dma();
+    PHASE_BARRIER();
+    if (grp == 1) PHASE_BARRIER();
+    qk_mfmas();                    // S^T of tile 0 (K buffer 0)
+    flip_k();                      // ka -> K buffer 1, where tile 1 is
+    PHASE_BARRIER();
+
+    for (int64_t j = 0; j + 1 < ntiles; ++j) {
+        const int par = (int)(j & 1);
+        // VALU phase of tile j
+        if (grp == 1) {
+            dma_v_tile(j + 1, par ^ 1, wig, W4{});
+            if (j + 2 < ntiles) dma_k_tile(j + 2, par, wig, W4{});
+        }
+        softmax_tile(j);
+        PHASE_BARRIER();
+        // MFMA phase: second product of tile j, first product of tile j+1
+        pv_mfmas();
+        qk_mfmas();
+        flip_k();
+        flip_v();
+        if (grp == 1) wait_dma();
+        PHASE_BARRIER();
     }
-    if (t < ntiles) tile_step(t, std::integral_constant<int, 0>{});
+    // last tile: no next tile to prefetch or to start
+    softmax_tile(ntiles - 1);
+    PHASE_BARRIER();
+    pv_mfmas();
+    PHASE_BARRIER();
+    if (grp == 0) PHASE_BARRIER();
 
     const float l_tot = xhalf_sum(l_run);
     const float inv = 1.0f / l_tot;
@@ -330,25 +410,34 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
 
 }  // namespace
 
-// The bf16 path stages nothing outside its inputs and outputs.
-size_t attn_bf16_workspace_bytes(int64_t, int32_t) { return 0; }
+// Workspace of the bf16 path: the V^T tiles written by the pre-pass.
+size_t attn_bf16_workspace_bytes(int64_t N, int32_t H)
+{
+    if (N <= 0 || H <= 0) return 0;
+    const int64_t ntiles = (N + kBk - 1) / kBk;
+    return (size_t)ntiles * (size_t)H * kTileBytes;
+}
 
 int launch_attn_bf16_d128(const void *q, const void *k, const void *v, int64_t N, int32_t H, int64_t q_stride_n,
                           int64_t q_stride_h, int64_t kv_stride_n, int64_t kv_stride_h, const int32_t *idx_sel,
-                          int64_t k_sel, int q_is_compact, float scale, void *o_sel, float *lse_sel, void *,
+                          int64_t k_sel, int q_is_compact, float scale, void *o_sel, float *lse_sel, void *workspace,
                           hipStream_t stream)
 {
     if (k_sel == 0) return ASTRAEA_OK;
     // a tile's lane offsets are 32-bit: 64 rows must span less than 4 GiB
     if (kv_stride_n * 2 * kBk >= (int64_t)1 << 32)
         return fail(ASTRAEA_ERR_UNSUPPORTED, "astraea_sparse_attn_fwd: K/V token stride too large");
+    const int64_t ntiles = (N + kBk - 1) / kBk;
     const int64_t q_tiles = (k_sel + kBq - 1) / kBq;
     const int64_t total = q_tiles * H;
     const int64_t per_xcd = (total + kNumXcd - 1) / kNumXcd;
-    if (per_xcd * kNumXcd > 2147483647LL) return fail(ASTRAEA_ERR_INVALID, "astraea_sparse_attn_fwd: grid too large");
+    if (per_xcd * kNumXcd > 2147483647LL || ntiles > 2147483647LL)
+        return fail(ASTRAEA_ERR_INVALID, "astraea_sparse_attn_fwd: grid too large");
+    hipLaunchKernelGGL(transpose_v_kernel, dim3((unsigned)ntiles, (unsigned)H), dim3(256), 0, stream,
+                       (const __bf16 *)v, N, kv_stride_n, kv_stride_h, ntiles, (char *)workspace);
     dim3 grid((unsigned)(per_xcd * kNumXcd)), block(kWaves * kWave);
     hipLaunchKernelGGL(attn_bf16_kernel, grid, block, 0, stream, (const __bf16 *)q, (const __bf16 *)k,
-                       (const __bf16 *)v, N, H, q_stride_n, q_stride_h, kv_stride_n, kv_stride_h, idx_sel, k_sel,
+                       (const char *)workspace, N, H, q_stride_n, q_stride_h, kv_stride_n, kv_stride_h, idx_sel, k_sel,
                        q_is_compact, scale * 1.44269504088896340736f, (__bf16 *)o_sel, lse_sel, (int32_t)q_tiles,
                        per_xcd);
     return check_launch("astraea_sparse_attn_fwd(bf16)");
