@@ -132,6 +132,22 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const __bf16 *__restri
     }
 }
 
+// Budget-aware work split.  Work item = (head, tile of 256 selected queries), head-major; XCD x owns the
+// contiguous item range [x * items_per_xcd, (x+1) * items_per_xcd) and workgroups reach XCDs round-robin
+// by id.  With 32 CUs per XCD the items of an XCD run in rounds of 32.  The first `full_items` of each
+// XCD sweep all keys; the remaining items_per_xcd - full_items (< 32, what would be a mostly idle last
+// round) are each cut into `splits` key ranges of `tiles_per_split` tiles, run by as many workgroups,
+// whose unnormalised partial results are combined by merge_partials_kernel.  Execution time then
+// follows the number of selected tokens instead of the number of rounds.
+struct AttnSchedule {
+    int64_t items_per_xcd;
+    int64_t full_items;
+    int64_t tiles_per_split;
+    int32_t q_tiles;
+    int32_t splits;
+};
+constexpr int kPartialFloats = kBq * D + 2 * kBq;    // O^T accumulators, then running max, then row sum
+
 constexpr int MFMA = 0x008, DSR = 0x100;
 #define SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
 // Nothing may be moved across a phase boundary: left alone, the scheduler pulls the exponentials next to
@@ -147,19 +163,27 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
     const __bf16 *__restrict__ q, const __bf16 *__restrict__ k, const char *__restrict__ vt, int64_t N, int32_t H,
     int64_t q_stride_n, int64_t q_stride_h, int64_t kv_stride_n, int64_t kv_stride_h,
     const int32_t *__restrict__ idx_sel, int64_t k_sel, int q_is_compact, float scale_log2e,
-    __bf16 *__restrict__ o_sel, float *__restrict__ lse_sel, int32_t q_tiles, int64_t items_per_xcd)
+    __bf16 *__restrict__ o_sel, float *__restrict__ lse_sel, AttnSchedule sch, float *__restrict__ partial)
 {
     // [parity][K tile | V^T tile]; 64 KiB, one 8-wave workgroup per CU (two waves per SIMD)
     __shared__ __attribute__((aligned(1024))) char lds[2 * kBufBytes];
 
-    // work item = (head, query tile), head-major; XCD x owns the contiguous item range
-    // [x * items_per_xcd, (x+1) * items_per_xcd), and workgroups reach XCDs round-robin by id.
-    const int64_t total_items = (int64_t)H * q_tiles;
+    const int64_t ntiles = (N + kBk - 1) / kBk;
+    const int64_t total_items = (int64_t)H * sch.q_tiles;
     const int64_t xcd = blockIdx.x % kNumXcd, slot = blockIdx.x / kNumXcd;
-    const int64_t item = xcd * items_per_xcd + slot;
-    if (slot >= items_per_xcd || item >= total_items) return;
-    const int head = (int)(item / q_tiles);
-    const int64_t qt = item % q_tiles;
+    int64_t item, tile_begin = 0, tile_end = ntiles, pslot = -1;
+    if (slot < sch.full_items) {
+        item = xcd * sch.items_per_xcd + slot;
+    } else {
+        const int64_t p = slot - sch.full_items, li = p / sch.splits, sp = p % sch.splits;
+        item = xcd * sch.items_per_xcd + sch.full_items + li;
+        tile_begin = sp * sch.tiles_per_split;
+        tile_end = tile_begin + sch.tiles_per_split < ntiles ? tile_begin + sch.tiles_per_split : ntiles;
+        pslot = (xcd * (sch.items_per_xcd - sch.full_items) + li) * sch.splits + sp;
+    }
+    if (item >= (xcd + 1) * sch.items_per_xcd || item >= total_items) return;
+    const int head = (int)(item / sch.q_tiles);
+    const int64_t qt = item % sch.q_tiles;
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
@@ -187,7 +211,6 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
     // ---- tile DMA.  A wave instruction fills 1 KiB of a tile: lane l writes 16 bytes at 16*l.
     // K: block = 4 key rows; physical chunk p of row r holds logical chunk p ^ (r & 15).
     // V^T: the pre-pass already wrote the tile as its LDS image, so the copy is linear.
-    const int64_t ntiles = (N + kBk - 1) / kBk;
     const char *kbase = reinterpret_cast<const char *>(k + (int64_t)head * kv_stride_h);
     const char *vtbase = vt + (int64_t)head * ntiles * kTileBytes;
     const int64_t row_pitch = kv_stride_n * 2;       // bytes between consecutive keys
@@ -286,10 +309,13 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
     };
 
     constexpr int kAhead = 4;      // an MFMA's fragment is fetched kAhead MFMAs before it issues
-    // O^T += V^T(j) P^T(j): 16 MFMAs; group tt contracts the 16 keys 16*tt + {0..3, 8..11} (lanes 0-31)
-    // and 16*tt + {4..7, 12..15} (lanes 32-63).  V^T(j) is in the parity va[] points at.
-    auto pv_mfmas = [&]() __attribute__((always_inline)) {
-        bf16x8 vf[16];
+    // MFMA phase.  O^T += V^T(j) P^T(j): 16 MFMAs; group tt contracts the 16 keys 16*tt + {0..3, 8..11}
+    // (lanes 0-31) and 16*tt + {4..7, 12..15} (lanes 32-63); V^T(j) is in the parity va[] points at.
+    // Then, if WITH_QK, S^T = K Q^T for the tile in the parity ka[] points at: 16 MFMAs, two blocks
+    // of 32 keys.  One LDS read pipeline runs through all 32 MFMAs.
+    auto mfma_phase = [&](auto qk_tag) __attribute__((always_inline)) {
+        constexpr bool WITH_QK = decltype(qk_tag)::value;
+        bf16x8 vf[16], kf[16];
 #pragma unroll
         for (int u = 0; u < kAhead; ++u) vf[u] = lds_read_b128(va[u >> 2] + (u & 3) * 32 * 128);
 #pragma unroll
@@ -297,39 +323,44 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
             const int tt = u >> 2, b = u & 3;
             uint4v p4 = {pw[4 * tt], pw[4 * tt + 1], pw[4 * tt + 2], pw[4 * tt + 3]};
             oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[u], __builtin_bit_cast(bf16x8, p4), oacc[b], 0, 0, 0);
-            if (u + kAhead < 16) vf[u + kAhead] = lds_read_b128(va[(u + kAhead) >> 2] + ((u + kAhead) & 3) * 32 * 128);
+            const int n = u + kAhead;
+            if (n < 16)
+                vf[n] = lds_read_b128(va[n >> 2] + (n & 3) * 32 * 128);
+            else if (WITH_QK)
+                kf[n - 16] = lds_read_b128(ka[(n - 16) & 7] + ((n - 16) >> 3) * 32 * kRowBytes);
+        }
+        if (WITH_QK) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                sacc[0][i] = 0.0f;
+                sacc[1][i] = 0.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                sacc[u >> 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[u], qf[u & 7], sacc[u >> 3], 0, 0, 0);
+                const int n = u + kAhead;
+                if (n < 16) kf[n] = lds_read_b128(ka[n & 7] + (n >> 3) * 32 * kRowBytes);
+            }
         }
         SGB(DSR, kAhead);
 #pragma unroll
-        for (int u = 0; u < 16 - kAhead; ++u) {
+        for (int u = 0; u < (WITH_QK ? 32 : 16) - kAhead; ++u) {
             SGB(MFMA, 1);
             SGB(DSR, 1);
         }
         SGB(MFMA, kAhead);
     };
-    // S^T = K Q^T for the tile in the parity ka[] points at: 16 MFMAs, two blocks of 32 keys
+    // S^T of tile 0 (prologue only)
     auto qk_mfmas = [&]() __attribute__((always_inline)) {
-        bf16x8 kf[16];
-#pragma unroll
-        for (int u = 0; u < kAhead; ++u) kf[u] = lds_read_b128(ka[u & 7] + (u >> 3) * 32 * kRowBytes);
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             sacc[0][i] = 0.0f;
             sacc[1][i] = 0.0f;
         }
 #pragma unroll
-        for (int u = 0; u < 16; ++u) {
-            sacc[u >> 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[u], qf[u & 7], sacc[u >> 3], 0, 0, 0);
-            if (u + kAhead < 16)
-                kf[u + kAhead] = lds_read_b128(ka[(u + kAhead) & 7] + ((u + kAhead) >> 3) * 32 * kRowBytes);
-        }
-        SGB(DSR, kAhead);
-#pragma unroll
-        for (int u = 0; u < 16 - kAhead; ++u) {
-            SGB(MFMA, 1);
-            SGB(DSR, 1);
-        }
-        SGB(MFMA, kAhead);
+        for (int u = 0; u < 16; ++u)
+            sacc[u >> 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                lds_read_b128(ka[u & 7] + (u >> 3) * 32 * kRowBytes), qf[u & 7], sacc[u >> 3], 0, 0, 0);
     };
     auto flip_k = [&]() __attribute__((always_inline)) {
 #pragma unroll
@@ -352,9 +383,9 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
     const int grp = wave >> 2, wig = wave & 3;
     using W4 = std::integral_constant<int, 4>;
     using W8 = std::integral_constant<int, 8>;
-    dma_k_tile(0, 0, wave, W8{});
-    dma_v_tile(0, 0, wave, W8{});
-    if (ntiles > 1) dma_k_tile(1, 1, wave, W8{});
+    dma_k_tile(tile_begin, 0, wave, W8{});
+    dma_v_tile(tile_begin, 0, wave, W8{});
+    if (tile_begin + 1 < tile_end) dma_k_tile(tile_begin + 1, 1, wave, W8{});
     // The Q fragment must be resident before the loop starts: a load still counted as pending at the
     // loop header would make the compiler wait on the vector-memory counter inside the loop.
 #pragma unroll
@@ -362,35 +393,54 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
     wait_dma();
     PHASE_BARRIER();
     if (grp == 1) PHASE_BARRIER();
-    qk_mfmas();                    // S^T of tile 0 (K buffer 0)
-    flip_k();                      // ka -> K buffer 1, where tile 1 is
+    qk_mfmas();                    // S^T of the first tile (K buffer 0)
+    flip_k();                      // ka -> K buffer 1, where the second tile is
     PHASE_BARRIER();
 
-    for (int64_t j = 0; j + 1 < ntiles; ++j) {
-        const int par = (int)(j & 1);
+    for (int64_t j = tile_begin; j + 1 < tile_end; ++j) {
+        const int par = (int)((j - tile_begin) & 1);
         // VALU phase of tile j
         if (grp == 1) {
             dma_v_tile(j + 1, par ^ 1, wig, W4{});
-            if (j + 2 < ntiles) dma_k_tile(j + 2, par, wig, W4{});
+            if (j + 2 < tile_end) dma_k_tile(j + 2, par, wig, W4{});
         }
         softmax_tile(j);
         PHASE_BARRIER();
-        // MFMA phase: second product of tile j, first product of tile j+1
-        pv_mfmas();
-        qk_mfmas();
+        // MFMA phase: second product of tile j, first product of tile j+1.  The wave in this phase
+        // gets issue priority over its SIMD neighbour, which is in its VALU phase.
+        __builtin_amdgcn_s_setprio(3);
+        mfma_phase(std::true_type{});
+        __builtin_amdgcn_s_setprio(0);
         flip_k();
         flip_v();
         if (grp == 1) wait_dma();
         PHASE_BARRIER();
     }
     // last tile: no next tile to prefetch or to start
-    softmax_tile(ntiles - 1);
+    softmax_tile(tile_end - 1);
     PHASE_BARRIER();
-    pv_mfmas();
+    mfma_phase(std::false_type{});
     PHASE_BARRIER();
     if (grp == 0) PHASE_BARRIER();
 
     const float l_tot = xhalf_sum(l_run);
+    if (pslot >= 0) {
+        // a key-range share of an item: unnormalised accumulators, running max and row sum go to the
+        // workspace; merge_partials_kernel combines the shares
+        float *pp = partial + pslot * kPartialFloats;
+        const int row = wave * 32 + qc;
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+                *reinterpret_cast<float4 *>(pp + row * D + 32 * b + 8 * g + 4 * hf) =
+                    make_float4(oacc[b][4 * g], oacc[b][4 * g + 1], oacc[b][4 * g + 2], oacc[b][4 * g + 3]);
+        if (hf == 0) {
+            pp[kBq * D + row] = m_c;
+            pp[kBq * D + kBq + row] = l_tot;
+        }
+        return;
+    }
     const float inv = 1.0f / l_tot;
     const int64_t rr = r0 + qc;
     if (rr >= k_sel) return;
@@ -408,14 +458,62 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
     if (lse_sel && hf == 0) lse_sel[rr * H + head] = (m_c + log2f(l_tot)) * 0.69314718055994530942f;
 }
 
+
+// Combines the key-range shares of the split items: with m* = max_s m_s and w_s = 2^(m_s - m*),
+// O = sum_s w_s O_s / sum_s w_s l_s.  One workgroup per split item; thread t handles rows t/32 + 8*i
+// and four head-dim elements.
+__global__ __launch_bounds__(256) void merge_partials_kernel(const float *__restrict__ partial, AttnSchedule sch,
+                                                             int32_t H, int64_t k_sel, __bf16 *__restrict__ o_sel,
+                                                             float *__restrict__ lse_sel)
+{
+    const int64_t left = sch.items_per_xcd - sch.full_items;
+    const int64_t xcd = blockIdx.x / left, li = blockIdx.x % left;
+    const int64_t item = xcd * sch.items_per_xcd + sch.full_items + li;
+    if (item >= (xcd + 1) * sch.items_per_xcd || item >= (int64_t)H * sch.q_tiles) return;
+    const int head = (int)(item / sch.q_tiles);
+    const int64_t qt = item % sch.q_tiles;
+    const float *base = partial + (xcd * left + li) * sch.splits * (int64_t)kPartialFloats;
+    const int d4 = (threadIdx.x & 31) * 4;
+    for (int i = 0; i < kBq / 8; ++i) {
+        const int row = (threadIdx.x >> 5) + 8 * i;
+        const int64_t rr = qt * kBq + row;
+        if (rr >= k_sel) continue;
+        float m_star = -INFINITY;
+        for (int s = 0; s < sch.splits; ++s) m_star = fmaxf(m_star, base[s * (int64_t)kPartialFloats + kBq * D + row]);
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        float l = 0.0f;
+        for (int s = 0; s < sch.splits; ++s) {
+            const float *ps = base + s * (int64_t)kPartialFloats;
+            const float w = exp2f(ps[kBq * D + row] - m_star);
+            const float4 o = *reinterpret_cast<const float4 *>(ps + row * D + d4);
+            acc.x += w * o.x;
+            acc.y += w * o.y;
+            acc.z += w * o.z;
+            acc.w += w * o.w;
+            l += w * ps[kBq * D + kBq + row];
+        }
+        const float inv = 1.0f / l;
+        uint2v o4;
+        o4[0] = pack_bf16(acc.x * inv, acc.y * inv);
+        o4[1] = pack_bf16(acc.z * inv, acc.w * inv);
+        *reinterpret_cast<uint2v *>(o_sel + (rr * H + head) * (int64_t)D + d4) = o4;
+        if (lse_sel && d4 == 0) lse_sel[rr * H + head] = (m_star + log2f(l)) * 0.69314718055994530942f;
+    }
+}
+
 }  // namespace
 
-// Workspace of the bf16 path: the V^T tiles written by the pre-pass.
+// Workspace of the bf16 path: the V^T tiles written by the pre-pass, then the partial results of the
+// split items (at most 32 shares per XCD).
+static size_t vt_bytes(int64_t N, int32_t H)
+{
+    const int64_t ntiles = (N + kBk - 1) / kBk;
+    return (size_t)ntiles * (size_t)H * kTileBytes;
+}
 size_t attn_bf16_workspace_bytes(int64_t N, int32_t H)
 {
     if (N <= 0 || H <= 0) return 0;
-    const int64_t ntiles = (N + kBk - 1) / kBk;
-    return (size_t)ntiles * (size_t)H * kTileBytes;
+    return vt_bytes(N, H) + (size_t)kNumXcd * 32 * kPartialFloats * sizeof(float);
 }
 
 int launch_attn_bf16_d128(const void *q, const void *k, const void *v, int64_t N, int32_t H, int64_t q_stride_n,
@@ -428,18 +526,37 @@ int launch_attn_bf16_d128(const void *q, const void *k, const void *v, int64_t N
     if (kv_stride_n * 2 * kBk >= (int64_t)1 << 32)
         return fail(ASTRAEA_ERR_UNSUPPORTED, "astraea_sparse_attn_fwd: K/V token stride too large");
     const int64_t ntiles = (N + kBk - 1) / kBk;
-    const int64_t q_tiles = (k_sel + kBq - 1) / kBq;
-    const int64_t total = q_tiles * H;
-    const int64_t per_xcd = (total + kNumXcd - 1) / kNumXcd;
-    if (per_xcd * kNumXcd > 2147483647LL || ntiles > 2147483647LL)
+    constexpr int kCuPerXcd = 32;
+    AttnSchedule sch;
+    sch.q_tiles = (int32_t)((k_sel + kBq - 1) / kBq);
+    const int64_t total = (int64_t)sch.q_tiles * H;
+    sch.items_per_xcd = (total + kNumXcd - 1) / kNumXcd;
+    // items that would run in a last, partly filled round are cut along the keys so that the round fills
+    int64_t left = sch.items_per_xcd % kCuPerXcd;
+    int64_t splits = left > 0 ? kCuPerXcd / left : 1;
+    if (splits > ntiles) splits = ntiles;
+    while (splits > 1 && (splits - 1) * ((ntiles + splits - 1) / splits) >= ntiles) --splits;
+    if (splits <= 1) {
+        left = 0;
+        splits = 1;
+    }
+    sch.full_items = sch.items_per_xcd - left;
+    sch.splits = (int32_t)splits;
+    sch.tiles_per_split = (ntiles + splits - 1) / splits;
+    const int64_t slots = sch.full_items + left * splits;
+    if (slots * kNumXcd > 2147483647LL || ntiles > 2147483647LL)
         return fail(ASTRAEA_ERR_INVALID, "astraea_sparse_attn_fwd: grid too large");
+    char *vt = (char *)workspace;
+    float *partial = (float *)(vt + vt_bytes(N, H));
     hipLaunchKernelGGL(transpose_v_kernel, dim3((unsigned)ntiles, (unsigned)H), dim3(256), 0, stream,
-                       (const __bf16 *)v, N, kv_stride_n, kv_stride_h, ntiles, (char *)workspace);
-    dim3 grid((unsigned)(per_xcd * kNumXcd)), block(kWaves * kWave);
+                       (const __bf16 *)v, N, kv_stride_n, kv_stride_h, ntiles, vt);
+    dim3 grid((unsigned)(slots * kNumXcd)), block(kWaves * kWave);
     hipLaunchKernelGGL(attn_bf16_kernel, grid, block, 0, stream, (const __bf16 *)q, (const __bf16 *)k,
-                       (const char *)workspace, N, H, q_stride_n, q_stride_h, kv_stride_n, kv_stride_h, idx_sel, k_sel,
-                       q_is_compact, scale * 1.44269504088896340736f, (__bf16 *)o_sel, lse_sel, (int32_t)q_tiles,
-                       per_xcd);
+                       (const char *)vt, N, H, q_stride_n, q_stride_h, kv_stride_n, kv_stride_h, idx_sel, k_sel,
+                       q_is_compact, scale * 1.44269504088896340736f, (__bf16 *)o_sel, lse_sel, sch, partial);
+    if (left > 0)
+        hipLaunchKernelGGL(merge_partials_kernel, dim3((unsigned)(left * kNumXcd)), dim3(256), 0, stream, partial, sch,
+                           H, k_sel, (__bf16 *)o_sel, lse_sel);
     return check_launch("astraea_sparse_attn_fwd(bf16)");
 }
 
