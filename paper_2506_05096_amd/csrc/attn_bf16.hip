@@ -306,6 +306,9 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
                 ps0 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pw[u]), ones, ps0, false);
         }
         l_run += ps0 + ps1;
+        // keep the row-sum arithmetic in this phase (it is not needed until the end of the sweep, and
+        // would otherwise drift behind the MFMAs of the next phase)
+        asm volatile("" : "+v"(l_run));
     };
 
     constexpr int kAhead = 4;      // an MFMA's fragment is fetched kAhead MFMAs before it issues
@@ -362,13 +365,20 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
             sacc[u >> 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                 lds_read_b128(ka[u & 7] + (u >> 3) * 32 * kRowBytes), qf[u & 7], sacc[u >> 3], 0, 0, 0);
     };
+    // the asm pins keep the address updates where they are written (in a VALU phase)
     auto flip_k = [&]() __attribute__((always_inline)) {
 #pragma unroll
-        for (int s = 0; s < D / 16; ++s) ka[s] ^= kBufBytes;
+        for (int s = 0; s < D / 16; ++s) {
+            ka[s] ^= kBufBytes;
+            asm volatile("" : "+v"(ka[s]));
+        }
     };
     auto flip_v = [&]() __attribute__((always_inline)) {
 #pragma unroll
-        for (int tt = 0; tt < 4; ++tt) va[tt] ^= kBufBytes;
+        for (int tt = 0; tt < 4; ++tt) {
+            va[tt] ^= kBufBytes;
+            asm volatile("" : "+v"(va[tt]));
+        }
     };
 
     // ---- ping-pong schedule.  K tile j lives in K buffer j & 1, V^T tile j in V buffer j & 1.
@@ -404,6 +414,10 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
             dma_v_tile(j + 1, par ^ 1, wig, W4{});
             if (j + 2 < tile_end) dma_k_tile(j + 2, par, wig, W4{});
         }
+        if (j > tile_begin) {      // buffers swap roles after every MFMA phase
+            flip_k();
+            flip_v();
+        }
         softmax_tile(j);
         PHASE_BARRIER();
         // MFMA phase: second product of tile j, first product of tile j+1.  The wave in this phase
@@ -411,12 +425,14 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
         __builtin_amdgcn_s_setprio(3);
         mfma_phase(std::true_type{});
         __builtin_amdgcn_s_setprio(0);
-        flip_k();
-        flip_v();
         if (grp == 1) wait_dma();
         PHASE_BARRIER();
     }
     // last tile: no next tile to prefetch or to start
+    if (tile_end - tile_begin > 1) {
+        flip_k();
+        flip_v();
+    }
     softmax_tile(tile_end - 1);
     PHASE_BARRIER();
     mfma_phase(std::false_type{});
