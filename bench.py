@@ -25,8 +25,8 @@ METRIC = "selected-token attn TFLOP/s (% MFMA peak) + ms/layer, N=118800 H=24 D=
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}     # MI355X dense MFMA peaks
 PEAK_HBM_GBS = 8000.0
 # HBM bytes one launch of the dominant kernel moves, from rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by
-# what the same counter reads for the library's plain 1 GiB copy (profiles/hot_path_cfg3_hbm_traffic.txt).
-MEASURED_TRAFFIC_BYTES = {("cfg3", 30): 8.01e9 + 0.219e9}
+# what the same counter reads for the library's plain 1 GiB copy (profiles/hot_path_cfg3_hbm_traffic_and_mfma.txt).
+MEASURED_TRAFFIC_BYTES = {("cfg3", 30): 8.03e9 + 0.252e9}
 
 
 def _np(t):
@@ -209,7 +209,9 @@ def main() -> int:
                      "frac": achieved / peak, "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, budget)),
                      "traffic_unit": "bytes per launch (algorithmic: (2k+2N)*H*D*2 = %.3g)" % ((2 * k + 2 * w.N) * row_bytes),
                      "kernel": "attn_bf16_kernel" if w.dtype == "bf16" else "attn_f32_kernel",
-                     "kernel_ms": attn_ms, "flops_per_launch": flops},
+                     "kernel_ms": attn_ms, "flops_per_launch": flops,
+                     "timed": "HIP events around astraea_sparse_attn_fwd: the dominant kernel plus, for bf16, its "
+                              "V re-tiling pre-pass and partial-result merge (<1 % of the call)"},
         "breakdown_ms": br,
         "hbm_GBps": gbs,
         "hbm_frac_of_8TBps": {k_: v_ / PEAK_HBM_GBS for k_, v_ in gbs.items()},

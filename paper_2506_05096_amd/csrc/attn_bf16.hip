@@ -476,8 +476,8 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
 
 
 // Combines the key-range shares of the split items: with m* = max_s m_s and w_s = 2^(m_s - m*),
-// O = sum_s w_s O_s / sum_s w_s l_s.  One workgroup per split item; thread t handles rows t/32 + 8*i
-// and four head-dim elements.
+// O = sum_s w_s O_s / sum_s w_s l_s.  Workgroup (x, y) handles rows 8*y .. 8*y+7 of split item x; a
+// thread handles one row and four head-dim elements.
 __global__ __launch_bounds__(256) void merge_partials_kernel(const float *__restrict__ partial, AttnSchedule sch,
                                                              int32_t H, int64_t k_sel, __bf16 *__restrict__ o_sel,
                                                              float *__restrict__ lse_sel)
@@ -490,10 +490,10 @@ __global__ __launch_bounds__(256) void merge_partials_kernel(const float *__rest
     const int64_t qt = item % sch.q_tiles;
     const float *base = partial + (xcd * left + li) * sch.splits * (int64_t)kPartialFloats;
     const int d4 = (threadIdx.x & 31) * 4;
-    for (int i = 0; i < kBq / 8; ++i) {
-        const int row = (threadIdx.x >> 5) + 8 * i;
+    {
+        const int row = (threadIdx.x >> 5) + 8 * blockIdx.y;
         const int64_t rr = qt * kBq + row;
-        if (rr >= k_sel) continue;
+        if (rr >= k_sel) return;
         float m_star = -INFINITY;
         for (int s = 0; s < sch.splits; ++s) m_star = fmaxf(m_star, base[s * (int64_t)kPartialFloats + kBq * D + row]);
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -571,7 +571,7 @@ int launch_attn_bf16_d128(const void *q, const void *k, const void *v, int64_t N
                        (const char *)vt, N, H, q_stride_n, q_stride_h, kv_stride_n, kv_stride_h, idx_sel, k_sel,
                        q_is_compact, scale * 1.44269504088896340736f, (__bf16 *)o_sel, lse_sel, sch, partial);
     if (left > 0)
-        hipLaunchKernelGGL(merge_partials_kernel, dim3((unsigned)(left * kNumXcd)), dim3(256), 0, stream, partial, sch,
+        hipLaunchKernelGGL(merge_partials_kernel, dim3((unsigned)(left * kNumXcd), kBq / 8), dim3(256), 0, stream, partial, sch,
                            H, k_sel, (__bf16 *)o_sel, lse_sel);
     return check_launch("astraea_sparse_attn_fwd(bf16)");
 }
