@@ -113,7 +113,7 @@ int astraea_select_topk(const float *score, int64_t N, int64_t k, int32_t *idx_s
  *   lse_sel     [k_sel, H] fp32 natural-log sum of exponentials of the scaled logits, or NULL.
  *   workspace   at least astraea_workspace_bytes(ASTRAEA_OP_SPARSE_ATTN, N, k_sel, H, D) bytes,
  *               256-byte aligned (may be NULL when that is 0).  The bf16 path stages a re-tiled
- *               copy of V there (N rounded up to 64, times H*D*2 bytes) plus 34 MB of partial
+ *               copy of V there (N rounded up to 64, times H*D*2 bytes) plus 68 MB of partial
  *               results on every call; contents need not be initialised and are clobbered.
  * Supported: (BF16, D = 128) on bf16 MFMA with fp32 softmax and accumulation;
  * (F32, D = 64 or 128) on fp32 MFMA.  k_sel == 0 enqueues nothing.

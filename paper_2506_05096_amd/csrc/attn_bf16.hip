@@ -147,6 +147,7 @@ struct AttnSchedule {
     int32_t splits;
 };
 constexpr int kPartialFloats = kBq * D + 2 * kBq;    // O^T accumulators, then running max, then row sum
+constexpr int kMaxSharesPerXcd = 64;
 
 constexpr int MFMA = 0x008, DSR = 0x100;
 #define SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
@@ -520,7 +521,7 @@ __global__ __launch_bounds__(256) void merge_partials_kernel(const float *__rest
 }  // namespace
 
 // Workspace of the bf16 path: the V^T tiles written by the pre-pass, then the partial results of the
-// split items (at most 32 shares per XCD).
+// split items (at most kMaxSharesPerXcd shares per XCD).
 static size_t vt_bytes(int64_t N, int32_t H)
 {
     const int64_t ntiles = (N + kBk - 1) / kBk;
@@ -529,7 +530,7 @@ static size_t vt_bytes(int64_t N, int32_t H)
 size_t attn_bf16_workspace_bytes(int64_t N, int32_t H)
 {
     if (N <= 0 || H <= 0) return 0;
-    return vt_bytes(N, H) + (size_t)kNumXcd * 32 * kPartialFloats * sizeof(float);
+    return vt_bytes(N, H) + (size_t)kNumXcd * kMaxSharesPerXcd * kPartialFloats * sizeof(float);
 }
 
 int launch_attn_bf16_d128(const void *q, const void *k, const void *v, int64_t N, int32_t H, int64_t q_stride_n,
@@ -547,11 +548,22 @@ int launch_attn_bf16_d128(const void *q, const void *k, const void *v, int64_t N
     sch.q_tiles = (int32_t)((k_sel + kBq - 1) / kBq);
     const int64_t total = (int64_t)sch.q_tiles * H;
     sch.items_per_xcd = (total + kNumXcd - 1) / kNumXcd;
-    // items that would run in a last, partly filled round are cut along the keys so that the round fills
+    // Items that would run in a last, partly filled round are cut along the keys into `splits` shares
+    // each, chosen (up to 8 shares per item, 64 shares per XCD) so that the shares take the fewest
+    // rounds relative to their length: rounds(left * splits) / splits is the tail's cost in full sweeps.
     int64_t left = sch.items_per_xcd % kCuPerXcd;
-    int64_t splits = left > 0 ? kCuPerXcd / left : 1;
-    if (splits > ntiles) splits = ntiles;
-    while (splits > 1 && (splits - 1) * ((ntiles + splits - 1) / splits) >= ntiles) --splits;
+    int64_t splits = 1;
+    if (left > 0) {
+        double best = 1.0;
+        for (int64_t s2 = 2; s2 <= 8 && left * s2 <= kMaxSharesPerXcd && s2 <= ntiles; ++s2) {
+            if ((s2 - 1) * ((ntiles + s2 - 1) / s2) >= ntiles) continue;      // would leave an empty share
+            const double cost = (double)((left * s2 + kCuPerXcd - 1) / kCuPerXcd) / (double)s2;
+            if (cost < best - 1e-9) {
+                best = cost;
+                splits = s2;
+            }
+        }
+    }
     if (splits <= 1) {
         left = 0;
         splits = 1;
