@@ -103,6 +103,44 @@ def measured_peaks(torch, ab, copy_reps=2):
     return out
 
 
+def library_context(torch, w, k):
+    """Context only, same GPU and shape: the vendor libraries PyTorch dispatches to (a bf16 GEMM and the
+    library flash attention) on dense tensors of the workload's shape.  Not part of the path."""
+    dev = "cuda:0"
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    out = {}
+    n = 8192
+    a = torch.randn(n, n, device=dev).bfloat16()
+    b = torch.randn(n, n, device=dev).bfloat16()
+    for _ in range(3):
+        a @ b
+    e0, e1 = ev(), ev()
+    e0.record()
+    for _ in range(20):
+        a @ b
+    e1.record()
+    torch.cuda.synchronize()
+    out["torch_matmul_bf16_8192_TFLOPs"] = 2.0 * n ** 3 / (e0.elapsed_time(e1) / 20) / 1e9
+    del a, b
+    if w.dtype == "bf16":
+        q = torch.randn(1, w.H, k, w.D, device=dev).bfloat16()
+        kk = torch.randn(1, w.H, w.N, w.D, device=dev).bfloat16()
+        vv = torch.randn(1, w.H, w.N, w.D, device=dev).bfloat16()
+        sdpa = torch.nn.functional.scaled_dot_product_attention
+        for _ in range(2):
+            sdpa(q, kk, vv)
+        e0, e1 = ev(), ev()
+        e0.record()
+        for _ in range(3):
+            sdpa(q, kk, vv)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 3
+        out["torch_sdpa_bf16_same_shape_ms"] = ms
+        out["torch_sdpa_bf16_same_shape_TFLOPs"] = 4.0 * k * w.N * w.D * w.H / ms / 1e9
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -114,6 +152,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--sweep", action="store_true", help="config 4: 50-step budget schedule")
+    ap.add_argument("--context", action="store_true",
+                    help="also time the vendor-library GEMM and flash attention PyTorch dispatches to (context only)")
     ap.add_argument("--calibrate", action="store_true",
                     help="only run the measurement aids: 1 GiB plain copy (x3) and the MFMA loop")
     args = ap.parse_args()
@@ -217,6 +257,8 @@ def main() -> int:
         "hbm_frac_of_8TBps": {k_: v_ / PEAK_HBM_GBS for k_, v_ in gbs.items()},
     }
     out["measured_peaks"] = measured_peaks(torch, ab)
+    if args.context:
+        out["library_context_same_gpu"] = library_context(torch, w, k)
     if not args.no_cpu_baseline:
         idx_host = layer.idx_sel[:k].cpu().numpy()
         out["cpu_baseline"] = cpu_baseline(w, t, idx_host, k, layer.scale, args.cpu_seconds)
