@@ -139,6 +139,20 @@ int astraea_scatter_update(void *cache, const void *src, astraea_dtype dt, int64
                            int64_t k_sel, int src_is_full, void *stream);
 
 /*
+ * astraea_lse_weight_update - carries the softmax by-product S_LSE of the selection metric to the
+ * next timestep (Sec. 3.2 "Selection Metric": S_sig = S_LSE,t-1 * Delta_token,t, where S_LSE is the
+ * row sum of exponentials the softmax computes anyway).  For every selected token
+ *     lse_weight[idx_sel[r]] = (1/H) * sum_h exp(lse_sel[r, h] - ln N),
+ * the mean over heads of the row's mean exponential (the paper does not say how heads combine; the
+ * 1/N keeps the value near 1 and does not change any ranking).  Tokens not selected keep the weight
+ * of the last step they were computed in.  The sum runs over h ascending in fp32.
+ *   lse_sel     [k_sel, H] fp32, as written by astraea_sparse_attn_fwd.
+ *   lse_weight  [N] fp32 in/out, the array astraea_score reads.
+ */
+int astraea_lse_weight_update(const float *lse_sel, int32_t H, int64_t N, const int32_t *idx_sel, int64_t k_sel,
+                              float *lse_weight, void *stream);
+
+/*
  * astraea_gather_rows - dst[r, :] = src[idx_sel[r], :] (Algorithm 1 step 5, X_in[I_sel]).
  */
 int astraea_gather_rows(const void *src, void *dst, astraea_dtype dt, int64_t N, int64_t row_elems,

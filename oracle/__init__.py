@@ -46,6 +46,7 @@ def lib() -> C.CDLL:
         L.oracle_update_skip_count.argtypes = [vp, vp, i64]
         L.oracle_sparse_attn.argtypes = [vp, vp, vp, C.c_int, i64, i32, i32, i64, i64, i64, i64, vp, i64, C.c_int,
                                          f32, C.c_int, vp, vp]
+        L.oracle_lse_weight_update.argtypes = [vp, i32, i64, vp, i64, vp]
         L.oracle_round_to_dtype.argtypes = [vp, i64, C.c_int, vp]
         L.oracle_scatter.argtypes = [vp, vp, C.c_int, i64, i64, i64, i64, vp, i64, C.c_int]
         L.oracle_gather.argtypes = [vp, vp, C.c_int, i64, i64, i64, i64, vp, i64]
@@ -147,6 +148,15 @@ def sparse_attn(q: np.ndarray, k: np.ndarray, v: np.ndarray, idx_sel, scale: flo
                                     _ptr(idx), k_sel, 1 if q_is_compact else 0, scale, 0 if acc == "f64" else 1,
                                     _ptr(o), _ptr(lse)), "oracle_sparse_attn")
     return o, lse
+
+
+def lse_weight_update(lse_weight: np.ndarray, lse_sel: np.ndarray, idx_sel) -> None:
+    """In place: lse_weight[idx[r]] = mean_h exp(lse_sel[r,h] - ln N)."""
+    assert lse_weight.dtype == np.float32 and lse_weight.flags.c_contiguous
+    lse = np.ascontiguousarray(lse_sel, dtype=np.float64)
+    idx = np.ascontiguousarray(idx_sel, dtype=np.int32)
+    _check(lib().oracle_lse_weight_update(_ptr(lse), lse.shape[1], lse_weight.shape[0], _ptr(idx), idx.shape[0],
+                                          _ptr(lse_weight)), "oracle_lse_weight_update")
 
 
 def round_to_dtype(x64: np.ndarray, dtype_code: int) -> np.ndarray:

@@ -12,6 +12,7 @@
  *                                                                             softmax as in the Self-Attention equations)
  *   oracle_scatter      X_out,t[I_sel] <- fresh rows, X_out,t[I_remain] kept (Algorithm 1, cache reuse step)
  *   oracle_gather       X[I_sel]                                             (Algorithm 1, query selection)
+ *   oracle_lse_weight_update  per-token S_LSE carried to the next step          (selection metric, S_sig equation)
  *
  * Precision.  Attention accumulates in fp64 (acc_mode 0) or in fp32 (acc_mode 1,
  * the "naive fp32" form); its outputs are returned as fp64.  The score is a
@@ -362,6 +363,27 @@ int oracle_round_to_dtype(const double *src, int64_t n, int dtype, void *dst)
     } else {
         for (int64_t i = 0; i < n; ++i)
             ((uint16_t *)dst)[i] = double_to_bf16_bits(src[i]);
+    }
+    return 0;
+}
+
+/*
+ * Per-token S_LSE carried to the next step (Sec. 3.2 "Selection Metric"; the softmax row sum is the
+ * by-product the paper reuses).  Reading taken for H heads: the mean over heads of the mean
+ * exponential, weight[idx[r]] = (1/H) sum_h exp(lse[r,h] - ln N); evaluated in fp64, stored as fp32.
+ */
+int oracle_lse_weight_update(const double *lse_sel, int32_t H, int64_t N, const int32_t *idx_sel, int64_t k_sel,
+                             float *lse_weight)
+{
+    if (N <= 0 || H <= 0 || k_sel < 0)
+        return -1;
+    for (int64_t r = 0; r < k_sel; ++r) {
+        double acc = 0.0;
+        for (int32_t h = 0; h < H; ++h)
+            acc += exp(lse_sel[r * H + h] - log((double)N));
+        if (idx_sel[r] < 0 || idx_sel[r] >= N)
+            return -1;
+        lse_weight[idx_sel[r]] = (float)(acc / (double)H);
     }
     return 0;
 }

@@ -25,7 +25,7 @@ OP_SELECT_TOPK, OP_SPARSE_ATTN = 1, 2
 EXPORTS = (
     "astraea_score", "astraea_select_topk", "astraea_sparse_attn_fwd", "astraea_scatter_update",
     "astraea_gather_rows", "astraea_workspace_bytes", "astraea_budget_to_k", "astraea_attn_flops",
-    "astraea_probe_mfma_bf16", "astraea_probe_copy",
+    "astraea_probe_mfma_bf16", "astraea_probe_copy", "astraea_lse_weight_update",
     "astraea_status_string", "astraea_last_error",
 )
 
@@ -63,6 +63,8 @@ def lib() -> C.CDLL:
         L.astraea_status_string.argtypes = [C.c_int]
         L.astraea_status_string.restype = C.c_char_p
         L.astraea_last_error.restype = C.c_char_p
+        L.astraea_lse_weight_update.argtypes = [vp, i32, i64, vp, i64, vp, vp]
+        L.astraea_lse_weight_update.restype = C.c_int
         L.astraea_probe_mfma_bf16.argtypes = [i32, i32, i32, vp, i64, C.POINTER(C.c_double), vp]
         L.astraea_probe_copy.argtypes = [vp, vp, i64, vp]
         L.astraea_probe_mfma_bf16.restype = C.c_int
@@ -153,6 +155,13 @@ def astraea_gather_rows(src: torch.Tensor, dst: torch.Tensor, idx_sel: torch.Ten
     assert src.dtype == dst.dtype and src.shape[1] == dst.shape[1]
     _check(lib().astraea_gather_rows(_p(src), _p(dst), _dt(src), src.shape[0], src.shape[1], src.stride(0),
                                      dst.stride(0), _p(idx_sel), k_sel, _stream()))
+
+
+def astraea_lse_weight_update(lse_sel: torch.Tensor, idx_sel: torch.Tensor, k_sel: int, lse_weight: torch.Tensor) -> None:
+    assert lse_sel.dtype == torch.float32 and lse_sel.is_contiguous() and lse_weight.dtype == torch.float32
+    H = lse_sel.shape[1]
+    _check(lib().astraea_lse_weight_update(_p(lse_sel), H, lse_weight.numel(), _p(idx_sel), k_sel, _p(lse_weight),
+                                           _stream()))
 
 
 def astraea_probe_mfma_bf16(workgroups: int, iters: int, randomize: bool, sink: torch.Tensor) -> float:

@@ -155,6 +155,21 @@ int astraea_gather_rows(const void *src, void *dst, astraea_dtype dt, int64_t N,
                             true, (hipStream_t)stream);
 }
 
+int astraea_lse_weight_update(const float *lse_sel, int32_t H, int64_t N, const int32_t *idx_sel, int64_t k_sel,
+                              float *lse_weight, void *stream)
+{
+    const char *fn = "astraea_lse_weight_update";
+    if (N <= 0 || N > kMaxTokens) return fail(ASTRAEA_ERR_INVALID, "%s: N=%lld out of range", fn, (long long)N);
+    if (H <= 0) return fail(ASTRAEA_ERR_INVALID, "%s: H=%d out of range", fn, (int)H);
+    if (k_sel < 0 || k_sel > N)
+        return fail(ASTRAEA_ERR_INVALID, "%s: k_sel=%lld not in [0, N=%lld]", fn, (long long)k_sel, (long long)N);
+    if (k_sel == 0) return ASTRAEA_OK;
+    if (!lse_sel || !idx_sel || !lse_weight) return fail(ASTRAEA_ERR_INVALID, "%s: NULL tensor", fn);
+    if (((uintptr_t)lse_sel | (uintptr_t)idx_sel | (uintptr_t)lse_weight) % 4 != 0)
+        return fail(ASTRAEA_ERR_INVALID, "%s: pointer not 4-byte aligned", fn);
+    return launch_lse_weight_update(lse_sel, H, N, idx_sel, k_sel, lse_weight, (hipStream_t)stream);
+}
+
 size_t astraea_workspace_bytes(int op, int64_t N, int64_t k_sel, int32_t H, int32_t D)
 {
     if (N < 0) return 0;

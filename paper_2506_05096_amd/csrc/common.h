@@ -29,6 +29,9 @@ int launch_move_rows(void *dst, const void *src, int64_t row_bytes, int64_t dst_
                      int64_t src_stride_bytes, const int32_t *idx, int64_t k_sel, bool index_dst, bool index_src,
                      hipStream_t stream);
 
+int launch_lse_weight_update(const float *lse_sel, int32_t H, int64_t N, const int32_t *idx_sel, int64_t k_sel,
+                             float *lse_weight, hipStream_t stream);
+
 size_t attn_bf16_workspace_bytes(int64_t N, int32_t H);
 int launch_attn_bf16_d128(const void *q, const void *k, const void *v, int64_t N, int32_t H, int64_t q_stride_n,
                           int64_t q_stride_h, int64_t kv_stride_n, int64_t kv_stride_h, const int32_t *idx_sel,

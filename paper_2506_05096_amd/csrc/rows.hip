@@ -1,4 +1,4 @@
-// Row movers behind astraea_gather_rows and astraea_scatter_update
+// Row movers behind astraea_gather_rows and astraea_scatter_update, and the per-token S_LSE update
 // (paper, Algorithm 1: X_in[I_sel] in step 5, and the cache merge of steps 6-7).
 //
 // A token row (H*D elements, 6 KiB for 24 heads x 128 x bf16) is contiguous, so the copy is fully
@@ -45,7 +45,28 @@ __global__ __launch_bounds__(kRowsPerBlock *kWave) void move_rows_kernel(
     if (p < nvec) d[p] = s[p];
 }
 
+// lse_weight[idx[r]] = mean over heads of exp(lse[r, h] - ln N); one thread per selected token.
+__global__ __launch_bounds__(256) void lse_weight_kernel(const float *__restrict__ lse_sel, int32_t H, float log_n,
+                                                         const int32_t *__restrict__ idx, int64_t k_sel,
+                                                         float *__restrict__ lse_weight)
+{
+    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= k_sel) return;
+    float acc = 0.0f;
+    for (int h = 0; h < H; ++h) acc += expf(lse_sel[r * H + h] - log_n);
+    lse_weight[idx[r]] = acc / (float)H;
+}
+
 }  // namespace
+
+int launch_lse_weight_update(const float *lse_sel, int32_t H, int64_t N, const int32_t *idx_sel, int64_t k_sel,
+                             float *lse_weight, hipStream_t stream)
+{
+    if (k_sel == 0) return ASTRAEA_OK;
+    hipLaunchKernelGGL(lse_weight_kernel, dim3((unsigned)((k_sel + 255) / 256)), dim3(256), 0, stream, lse_sel, H,
+                       logf((float)N), idx_sel, k_sel, lse_weight);
+    return check_launch("astraea_lse_weight_update");
+}
 
 int launch_move_rows(void *dst, const void *src, int64_t row_bytes, int64_t dst_stride_bytes,
                      int64_t src_stride_bytes, const int32_t *idx, int64_t k_sel, bool index_dst, bool index_src,

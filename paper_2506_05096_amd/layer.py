@@ -61,3 +61,41 @@ class LayerStep:
         self.step_kv_refresh(t, k)
         self.step_attn(t, k)
         self.step_scatter(t, k)
+
+
+class StatefulLayer(LayerStep):
+    """The layer-step with the state the full selection metric carries from one timestep to the next
+    (paper Sec. 3.2 "Selection Metric"): the features of the last step each token was computed in
+    (`x_ref`), the per-token softmax by-product S_LSE (`lse_weight`) and the count of consecutive
+    non-selections n_i (`skip_count`), whose penalty e^{n_i} comes from a table built by the caller."""
+
+    def __init__(self, N: int, H: int, D: int, C: int, dtype: torch.dtype, penalty_table: torch.Tensor,
+                 w_alpha: float = 1.0, w_beta: float = 0.0, device="cuda"):
+        super().__init__(N, H, D, dtype, device)
+        self.x_ref = torch.zeros((N, C), dtype=dtype, device=device)
+        self.lse_weight = torch.ones(N, dtype=torch.float32, device=device)
+        self.skip_count = torch.zeros(N, dtype=torch.int32, device=device)
+        self.lse_sel = torch.empty((N, H), dtype=torch.float32, device=device)
+        self.penalty_table = penalty_table.to(device=device, dtype=torch.float32)
+        self.w_alpha, self.w_beta = w_alpha, w_beta
+
+    def step_score(self, t: Dict[str, torch.Tensor]) -> None:
+        ab.astraea_score(t["x_cur"], self.x_ref, self.score, lse_weight=self.lse_weight, skip_count=self.skip_count,
+                         penalty_table=self.penalty_table, w_alpha=self.w_alpha, w_beta=self.w_beta)
+
+    def step_select(self, k: int) -> None:
+        ab.astraea_select_topk(self.score, k, self.idx_sel, self.topk_ws, skip_count=self.skip_count)
+
+    def step_state(self, t: Dict[str, torch.Tensor], k: int) -> None:
+        """After the attention: selected tokens were computed at this step, so their reference features and
+        their S_LSE are refreshed; the others keep what they had."""
+        ab.astraea_scatter_update(self.x_ref, t["x_cur"], self.idx_sel, k, src_is_full=True)
+        ab.astraea_lse_weight_update(self.lse_sel[:max(k, 1)], self.idx_sel, k, self.lse_weight)
+
+    def run(self, t: Dict[str, torch.Tensor], k: int) -> None:
+        self.step_score(t)
+        self.step_select(k)
+        self.step_kv_refresh(t, k)
+        self.step_attn(t, k, lse=self.lse_sel[:max(k, 1)])
+        self.step_state(t, k)
+        self.step_scatter(t, k)

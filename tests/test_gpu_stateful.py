@@ -1,0 +1,131 @@
+"""Multi-timestep state of the selection metric (paper Sec. 3.2 "Selection Metric"): S_LSE carried from
+the previous step, the consecutive non-selection counters n_i, and the features of the last computed step.
+
+The attention's log-sum-exp differs between the bf16 kernel and the fp64 oracle by ~1e-5, so from the second
+step on the two sides' scores differ in the last digits and near-ties may legitimately be cut differently.
+Each step therefore checks (a) GPU scores against oracle scores within a tolerance, (b) that the GPU's own
+selection is a valid top-k of the oracle's scores up to that tolerance, with exactly consistent counters,
+and then (c) continues both sides from the oracle's selection, so that all state stays comparable.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from conftest import bf16_bits_to_f64, to_np
+from paper_2506_05096_amd import binding as ab
+from paper_2506_05096_amd import synth
+from paper_2506_05096_amd.layer import StatefulLayer
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def test_lse_weight_update_matches_oracle():
+    g = torch.Generator().manual_seed(3)
+    n, h, k = 5000, 24, 1700
+    lse = (torch.randn(k, h, generator=g) * 2 + math.log(n)).float()
+    idx = torch.randperm(n, generator=g)[:k].sort().values.to(torch.int32)
+    w0 = torch.rand(n, generator=g) + 0.5
+    exp = w0.numpy().copy()
+    oracle.lse_weight_update(exp, lse.numpy().astype(np.float64), idx.numpy())
+    w = w0.to(DEV)
+    ab.astraea_lse_weight_update(lse.to(DEV), idx.to(DEV), k, w)
+    torch.cuda.synchronize()
+    got = w.cpu().numpy()
+    rest = np.setdiff1d(np.arange(n), idx.numpy())
+    assert np.array_equal(got[rest], exp[rest])                       # untouched tokens keep their bits
+    assert np.max(np.abs(got[idx.numpy()] - exp[idx.numpy()]) / exp[idx.numpy()]) < 2e-6
+    ab.astraea_lse_weight_update(lse.to(DEV), idx.to(DEV), 0, w)      # k = 0: nothing happens
+    torch.cuda.synchronize()
+    assert np.array_equal(w.cpu().numpy(), got)
+
+
+def test_five_steps_of_the_full_selection_metric():
+    n, H, D, Cw = 1536, 4, 128, 256
+    budgets = [50, 30, 70, 20, 40]
+    w_alpha, w_beta = 1.0, 0.05
+    table = oracle.penalty_table(16)
+    E = H * D
+    g = torch.Generator().manual_seed(21)
+    token_scale = torch.exp(0.7 * torch.randn(n, 1, generator=g))     # heavy-tailed per-token drift
+    x = torch.randn(n, Cw, generator=g)
+
+    layer = StatefulLayer(n, H, D, Cw, torch.bfloat16, torch.from_numpy(table), w_alpha, w_beta, device=DEV)
+    layer.x_ref.copy_(x.bfloat16())
+    wl = synth.Workload("state", "bf16", n, H, D, Cw, (50,), "drift")
+    t = synth.make_layer_inputs(wl, seed=5, device=DEV)
+    # oracle-side state
+    o_ref = to_np(x.bfloat16())
+    o_w = np.ones(n, np.float32)
+    o_cnt = np.zeros(n, np.int32)
+    o_k, o_v = to_np(t["k_cache"]).reshape(n, E).copy(), to_np(t["v_cache"]).reshape(n, E).copy()
+    o_out = bf16_bits_to_f64(to_np(t["out_cache"]))
+
+    for step, pct in enumerate(budgets):
+        x = x + 0.2 * token_scale * torch.randn(n, Cw, generator=g)
+        fresh = synth.make_layer_inputs(wl, seed=5, device=DEV, step=step + 1)
+        for name in ("q", "k_new", "v_new"):
+            t[name] = fresh[name]
+        t["x_cur"] = x.bfloat16().to(DEV)
+        h_cur, h_q = to_np(t["x_cur"]), to_np(t["q"])
+        h_kn, h_vn = to_np(t["k_new"]).reshape(n, E), to_np(t["v_new"]).reshape(n, E)
+        k = layer.budget_to_k(pct)
+
+        # (a) scores
+        so = oracle.score(h_cur, o_ref, oracle.DELTA_L2, lse_weight=o_w, skip_count=o_cnt, penalty_table=table,
+                          w_alpha=w_alpha, w_beta=w_beta)
+        layer.step_score(t)
+        torch.cuda.synchronize()
+        sg = layer.score.cpu().numpy()
+        tol = 0.0 if step == 0 else 1e-3            # step 0 has no carried S_LSE yet: bit-exact
+        assert np.max(np.abs(sg - so) / np.abs(so)) <= tol, (step, np.max(np.abs(sg - so) / np.abs(so)))
+
+        # (b) the GPU's selection is a valid top-k of the oracle's scores up to the tolerance
+        cnt_before = layer.skip_count.cpu().numpy().copy()
+        layer.step_select(k)
+        torch.cuda.synchronize()
+        gi = layer.idx_sel[:k].cpu().numpy()
+        assert np.all(np.diff(gi) > 0) and len(gi) == k
+        thr = np.sort(so)[::-1][k - 1]
+        mask_g = np.zeros(n, np.uint8)
+        mask_g[gi] = 1
+        assert so[gi].min() >= thr * (1 - 2 * tol) and so[mask_g == 0].max() <= thr * (1 + 2 * tol), step
+        assert np.array_equal(layer.skip_count.cpu().numpy(), oracle.update_skip_count(cnt_before, mask_g))
+        e_idx, _, e_mask = oracle.topk(so, k)
+        if step == 0:
+            assert np.array_equal(gi, e_idx)
+
+        # (c) continue both sides from the oracle's selection and counters
+        o_cnt = oracle.update_skip_count(o_cnt, e_mask)
+        layer.idx_sel[:k].copy_(torch.from_numpy(e_idx))
+        layer.skip_count.copy_(torch.from_numpy(o_cnt))
+        out_before = to_np(t["out_cache"]).copy()
+        layer.step_kv_refresh(t, k)
+        layer.step_attn(t, k, lse=layer.lse_sel[:k])
+        layer.step_state(t, k)
+        layer.step_scatter(t, k)
+        torch.cuda.synchronize()
+
+        oracle.scatter(o_k, h_kn, e_idx, src_is_full=True)
+        oracle.scatter(o_v, h_vn, e_idx, src_is_full=True)
+        o64, lse64 = oracle.sparse_attn(h_q, o_k.reshape(n, H, D), o_v.reshape(n, H, D), e_idx, layer.scale)
+        o_out[e_idx] = bf16_bits_to_f64(oracle.round_to_dtype(o64.reshape(k, E), oracle.BF16))
+        oracle.lse_weight_update(o_w, lse64, e_idx)
+        oracle.scatter(o_ref, h_cur, e_idx, src_is_full=True)
+
+        assert np.array_equal(to_np(t["k_cache"]).reshape(n, E), o_k) and np.array_equal(to_np(t["v_cache"]).reshape(n, E), o_v)
+        assert np.array_equal(to_np(layer.x_ref), o_ref), step
+        got_out = to_np(t["out_cache"])
+        rem = np.setdiff1d(np.arange(n), e_idx)
+        assert np.array_equal(got_out[rem], out_before[rem]), step              # unselected rows do not move
+        g64 = bf16_bits_to_f64(got_out)
+        rel = np.linalg.norm((g64[e_idx] - o_out[e_idx]).ravel()) / np.linalg.norm(o_out[e_idx].ravel())
+        assert rel <= 1e-2, (step, rel)
+        assert np.linalg.norm((g64 - o_out).ravel()) / np.linalg.norm(o_out.ravel()) <= 1e-2
+        gw = layer.lse_weight.cpu().numpy()
+        assert np.max(np.abs(gw - o_w) / o_w) <= 5e-4, (step, np.max(np.abs(gw - o_w) / o_w))
+        print(f"step {step}: budget {pct}% k={k} score tol {tol} attn rel {rel:.3g} "
+              f"lse-weight rel {np.max(np.abs(gw - o_w) / o_w):.2g} max n_i {o_cnt.max()}", flush=True)

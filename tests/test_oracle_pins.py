@@ -313,6 +313,31 @@ def test_attn_heads_and_operands_not_mixed():
     assert np.allclose(o[:, 1], v[5, 1].double().numpy()[None])
 
 
+def test_lse_weight_closed_forms_and_library():
+    """S_LSE carried between steps: mean over heads of the row's mean exponential."""
+    n, h = 50, 3
+    w = np.full(n, 7.0, np.float32)
+    idx = np.array([4, 9, 31], np.int32)
+    lse = np.empty((3, h))
+    lse[0] = math.log(n)                       # uniform attention in every head: sum of exponentials = N -> 1
+    lse[1] = math.log(2 * n)                   # -> 2
+    lse[2] = [math.log(n), math.log(3 * n), math.log(5 * n)]     # heads average: (1 + 3 + 5) / 3 = 3
+    oracle.lse_weight_update(w, lse, idx)
+    assert np.allclose(w[idx], [1.0, 2.0, 3.0], rtol=1e-6)
+    rest = np.setdiff1d(np.arange(n), idx)
+    assert np.all(w[rest] == 7.0)              # tokens not computed at this step keep their weight
+    # exp(lse) is the softmax row sum of exponentials (what the paper calls the LSE score): tie the update to
+    # the attention oracle's lse and to a library evaluation
+    q, k, v = _rand_qkv(40, 2, 8, 11)
+    sel = np.array([0, 5, 39], np.int32)
+    _, lse2 = oracle.sparse_attn(to_np(q), to_np(k), to_np(v), sel, 0.5)
+    s = 0.5 * torch.einsum("ihc,jhc->ihj", q.double(), k.double())
+    ref = (torch.exp(s).sum(dim=2) / 40).mean(dim=1).numpy()[sel]
+    w2 = np.zeros(40, np.float32)
+    oracle.lse_weight_update(w2, lse2, sel)
+    assert np.allclose(w2[sel], ref, rtol=1e-6)
+
+
 # ------------------------------------------------------- scatter / gather --
 
 @pytest.mark.parametrize("dt", [np.float32, np.uint16])
