@@ -254,12 +254,50 @@ def test_attn_bf16_peaked_and_uniform_rows():
     assert np.max(np.abs(lse - math.log(n))) < 1e-4
 
 
+@pytest.mark.parametrize("shape", ["ramp", "jump", "late_peak_after_floor"])
+def test_attn_bf16_logits_that_outgrow_the_first_tile(shape):
+    """The online softmax keeps a running row max that it only raises lazily; these rows make it rise far and
+    often.  Logits along one head-dim direction, so that their size is controlled exactly:
+    ramp  - logits rise by ~6 to ~23 nats per 128 keys (the max is raised many times);
+    jump  - flat, then single keys 35 to 283 nats above everything before them;
+    late_peak_after_floor - the first keys lie up to ~180 nats below the rest."""
+    n, h, d = 1500, 2, 128
+    g = torch.Generator().manual_seed(11)
+    v = torch.randn(n, h, d, generator=g)
+    k = 0.05 * torch.randn(n, h, d, generator=g)
+    q = 0.05 * torch.randn(n, h, d, generator=g)
+    a = torch.tensor([8.0, 16.0, 32.0]).repeat(n // 3)        # per-query gain
+    q[:, :, 0] = a[:, None]
+    j = torch.arange(n, dtype=torch.float32)
+    if shape == "ramp":
+        b = j / 16.0
+    elif shape == "jump":
+        b = torch.zeros(n)
+        b[700], b[1200], b[1499] = 50.0, 100.0, 99.0
+    else:
+        b = torch.full((n,), 64.0)
+        b[:128] = 0.0
+        b[900] = 70.0
+    k[:, :, 0] = b[:, None]
+    q, k, v = q.bfloat16(), k.bfloat16(), v.bfloat16()
+    idx = torch.arange(0, n, 2, dtype=torch.int32)
+    scale = 1.0 / math.sqrt(d)
+    eo, else_ = oracle.sparse_attn(to_np(q), to_np(k), to_np(v), idx.numpy(), scale)
+    o, lse = _run_attn(q, k, v, idx, scale)
+    assert np.all(np.isfinite(o)) and np.all(np.isfinite(lse))
+    assert _rel_l2(o, eo) <= 1e-2, _rel_l2(o, eo)
+    # lse is 50 to 280 here and the logits behind it reach 400 in the log2 units the kernel works in, where
+    # one fp32 ulp is 3e-5: a handful of roundings at that size
+    assert np.max(np.abs(lse - else_) / np.maximum(1.0, np.abs(else_))) <= 3e-5
+
+
 @pytest.mark.parametrize("n,h,k_sel", [
     (4100, 24, 1100),     # 5 query tiles x 24 heads = 15 items per XCD: a partly filled round, cut in 2 key ranges
     (1500, 8, 256),       # 1 item per XCD, cut into as many key ranges as there are tiles allow
     (700, 24, 2000 // 3), # 3 tiles x 24 heads = 9 items per XCD -> 3 key ranges of the 11 tiles (uneven split)
     (200, 3, 190),        # fewer items than XCDs
     (65, 5, 3),           # two tiles, one of them a single key
+    (129, 5, 3),          # three tiles, the last a single key
 ])
 def test_attn_bf16_split_items_match_oracle(n, h, k_sel):
     """Shapes chosen to exercise the budget-aware launch: items of the last round are cut along the keys

@@ -1,7 +1,7 @@
 """Multi-timestep state of the selection metric (paper Sec. 3.2 "Selection Metric"): S_LSE carried from
 the previous step, the consecutive non-selection counters n_i, and the features of the last computed step.
 
-The attention's log-sum-exp differs between the bf16 kernel and the fp64 oracle by ~1e-5, so from the second
+The attention's log-sum-exp differs between the bf16 kernel and the fp64 oracle by ~1e-5 to 1e-4, so from the second
 step on the two sides' scores differ in the last digits and near-ties may legitimately be cut differently.
 Each step therefore checks (a) GPU scores against oracle scores within a tolerance, (b) that the GPU's own
 selection is a valid top-k of the oracle's scores up to that tolerance, with exactly consistent counters,
