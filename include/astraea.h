@@ -126,6 +126,25 @@ int astraea_sparse_attn_fwd(const void *q, const void *k, const void *v, astraea
                             size_t workspace_bytes, void *stream);
 
 /*
+ * astraea_sparse_attn_update_fwd - the same attention with the cache merge fused into its last
+ * step (Algorithm 1 steps 6-7 as one operation: X_out,t[I_sel] = Softmax(Q_sel K^T / sqrt(d)) V while
+ * X_out,t[I_remain] keeps the cached rows): result row r is written straight to
+ *     out_cache[idx_sel[r], h*D : (h+1)*D]
+ * of the caller's per-token output buffer instead of to a compact array, which saves one write and one
+ * read of k_sel*H*D elements and the astraea_scatter_update call.  Bit-identical to
+ * astraea_sparse_attn_fwd followed by astraea_scatter_update(src_is_full = 0).
+ *   out_cache         [N, cache_row_stride] elements of dtype `dt`, rows not in idx_sel untouched;
+ *                     cache_row_stride >= H*D and a multiple of 8.
+ *   idx_sel           required (distinct, in [0, N)), also when q_is_compact == 1.
+ * All other arguments, limits and the workspace are those of astraea_sparse_attn_fwd.
+ */
+int astraea_sparse_attn_update_fwd(const void *q, const void *k, const void *v, astraea_dtype dt, int64_t N, int32_t H,
+                                   int32_t D, int64_t q_stride_n, int64_t q_stride_h, int64_t kv_stride_n,
+                                   int64_t kv_stride_h, const int32_t *idx_sel, int64_t k_sel, int q_is_compact,
+                                   float softmax_scale, void *out_cache, int64_t cache_row_stride, float *lse_sel,
+                                   void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * astraea_scatter_update - cache merge (Algorithm 1 steps 6-7): rows listed in idx_sel
  * are overwritten, every other row keeps what it held (the reuse of cached results).
  *   src_is_full == 0: cache[idx_sel[r], :] = src[r, :]            (src is [k_sel, row_elems])

@@ -23,8 +23,8 @@ OK, ERR_INVALID, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
 OP_SELECT_TOPK, OP_SPARSE_ATTN = 1, 2
 
 EXPORTS = (
-    "astraea_score", "astraea_select_topk", "astraea_sparse_attn_fwd", "astraea_scatter_update",
-    "astraea_gather_rows", "astraea_workspace_bytes", "astraea_budget_to_k", "astraea_attn_flops",
+    "astraea_score", "astraea_select_topk", "astraea_sparse_attn_fwd", "astraea_sparse_attn_update_fwd",
+    "astraea_scatter_update", "astraea_gather_rows", "astraea_workspace_bytes", "astraea_budget_to_k", "astraea_attn_flops",
     "astraea_probe_mfma_bf16", "astraea_probe_copy", "astraea_lse_weight_update",
     "astraea_status_string", "astraea_last_error",
 )
@@ -52,6 +52,8 @@ def lib() -> C.CDLL:
         L.astraea_select_topk.argtypes = [vp, i64, i64, vp, vp, vp, vp, vp, sz, vp]
         L.astraea_sparse_attn_fwd.argtypes = [vp, vp, vp, C.c_int, i64, i32, i32, i64, i64, i64, i64, vp, i64,
                                               C.c_int, f32, vp, vp, vp, sz, vp]
+        L.astraea_sparse_attn_update_fwd.argtypes = [vp, vp, vp, C.c_int, i64, i32, i32, i64, i64, i64, i64, vp, i64,
+                                                     C.c_int, f32, vp, i64, vp, vp, sz, vp]
         L.astraea_scatter_update.argtypes = [vp, vp, C.c_int, i64, i64, i64, i64, vp, i64, C.c_int, vp]
         L.astraea_gather_rows.argtypes = [vp, vp, C.c_int, i64, i64, i64, i64, vp, i64, vp]
         L.astraea_workspace_bytes.argtypes = [C.c_int, i64, i64, i32, i32]
@@ -69,8 +71,8 @@ def lib() -> C.CDLL:
         L.astraea_probe_copy.argtypes = [vp, vp, i64, vp]
         L.astraea_probe_mfma_bf16.restype = C.c_int
         L.astraea_probe_copy.restype = C.c_int
-        for name in ("astraea_score", "astraea_select_topk", "astraea_sparse_attn_fwd", "astraea_scatter_update",
-                     "astraea_gather_rows"):
+        for name in ("astraea_score", "astraea_select_topk", "astraea_sparse_attn_fwd",
+                     "astraea_sparse_attn_update_fwd", "astraea_scatter_update", "astraea_gather_rows"):
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -139,6 +141,21 @@ def astraea_sparse_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, i
     _check(lib().astraea_sparse_attn_fwd(_p(q), _p(k), _p(v), _dt(k), N, H, D, q.stride(0), q.stride(1), k.stride(0),
                                          k.stride(1), _p(idx_sel), k_sel, 1 if q_is_compact else 0, softmax_scale,
                                          _p(o_sel), _p(lse_sel), _p(workspace), wsb, _stream()))
+
+
+def astraea_sparse_attn_update_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, idx_sel: torch.Tensor,
+                                   k_sel: int, out_cache: torch.Tensor, softmax_scale: float,
+                                   q_is_compact: bool = False, lse_sel: Optional[torch.Tensor] = None,
+                                   workspace: Optional[torch.Tensor] = None) -> None:
+    N, H, D = k.shape
+    assert v.shape == k.shape and v.stride() == k.stride() and q.stride(2) == 1 and k.stride(2) == 1
+    assert q.dtype == k.dtype == v.dtype == out_cache.dtype
+    assert out_cache.dim() == 2 and out_cache.shape[0] == N and out_cache.shape[1] == H * D and out_cache.stride(1) == 1
+    wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().astraea_sparse_attn_update_fwd(_p(q), _p(k), _p(v), _dt(k), N, H, D, q.stride(0), q.stride(1),
+                                                k.stride(0), k.stride(1), _p(idx_sel), k_sel, 1 if q_is_compact else 0,
+                                                softmax_scale, _p(out_cache), out_cache.stride(0), _p(lse_sel),
+                                                _p(workspace), wsb, _stream()))
 
 
 def astraea_scatter_update(cache: torch.Tensor, src: torch.Tensor, idx_sel: torch.Tensor, k_sel: int,

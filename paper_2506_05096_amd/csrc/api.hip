@@ -78,27 +78,32 @@ int astraea_select_topk(const float *score, int64_t N, int64_t k, int32_t *idx_s
     return launch_select_topk(score, N, k, idx_sel, idx_remain, sel_mask, skip_count, workspace, (hipStream_t)stream);
 }
 
-int astraea_sparse_attn_fwd(const void *q, const void *k, const void *v, astraea_dtype dt, int64_t N, int32_t H,
-                            int32_t D, int64_t q_stride_n, int64_t q_stride_h, int64_t kv_stride_n,
-                            int64_t kv_stride_h, const int32_t *idx_sel, int64_t k_sel, int q_is_compact,
-                            float softmax_scale, void *o_sel, float *lse_sel, void *workspace,
-                            size_t workspace_bytes, void *stream)
+// Shared body of the two attention entry points: `out` is either the compact [k_sel, H, D] result
+// (scatter == 0, row stride H*D) or the cached per-token buffer [N, out_stride_n] whose rows idx_sel
+// names are overwritten (scatter == 1).
+static int sparse_attn_common(const char *fn, const void *q, const void *k, const void *v, astraea_dtype dt, int64_t N,
+                              int32_t H, int32_t D, int64_t q_stride_n, int64_t q_stride_h, int64_t kv_stride_n,
+                              int64_t kv_stride_h, const int32_t *idx_sel, int64_t k_sel, int q_is_compact,
+                              float softmax_scale, void *out, int64_t out_stride_n, int scatter, float *lse_sel,
+                              void *workspace, size_t workspace_bytes, void *stream)
 {
-    const char *fn = "astraea_sparse_attn_fwd";
     if (!dtype_ok(dt)) return fail(ASTRAEA_ERR_UNSUPPORTED, "%s: unknown dtype %d", fn, (int)dt);
     if (N <= 0 || N > kMaxTokens) return fail(ASTRAEA_ERR_INVALID, "%s: N=%lld out of range", fn, (long long)N);
     if (H <= 0 || H > 65535) return fail(ASTRAEA_ERR_INVALID, "%s: H=%d out of range", fn, (int)H);
-    if (k_sel < 0 || k_sel > kMaxTokens || (!q_is_compact && k_sel > N))
+    if (k_sel < 0 || k_sel > kMaxTokens || ((!q_is_compact || scatter) && k_sel > N))
         return fail(ASTRAEA_ERR_INVALID, "%s: k_sel=%lld out of range", fn, (long long)k_sel);
     if (!(dt == ASTRAEA_BF16 && D == 128) && !(dt == ASTRAEA_F32 && (D == 64 || D == 128)))
         return fail(ASTRAEA_ERR_UNSUPPORTED, "%s: no kernel for dtype %d with head_dim %d", fn, (int)dt, (int)D);
     if (!(softmax_scale > 0.0f) || !std::isfinite(softmax_scale))
         return fail(ASTRAEA_ERR_INVALID, "%s: softmax_scale must be positive and finite", fn);
+    if (scatter && (out_stride_n < (int64_t)H * D || out_stride_n % 8 != 0))
+        return fail(ASTRAEA_ERR_INVALID, "%s: cache_row_stride must be a multiple of 8 and at least H*D", fn);
     if (k_sel == 0) return ASTRAEA_OK;
-    if (!q || !k || !v || !o_sel) return fail(ASTRAEA_ERR_INVALID, "%s: NULL tensor", fn);
-    if (!q_is_compact && !idx_sel) return fail(ASTRAEA_ERR_INVALID, "%s: idx_sel is required to gather queries", fn);
-    if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o_sel) % 16 != 0)
-        return fail(ASTRAEA_ERR_INVALID, "%s: q, k, v, o_sel must be 16-byte aligned", fn);
+    if (!q || !k || !v || !out) return fail(ASTRAEA_ERR_INVALID, "%s: NULL tensor", fn);
+    if ((!q_is_compact || scatter) && !idx_sel)
+        return fail(ASTRAEA_ERR_INVALID, "%s: idx_sel is required to gather queries or to place rows", fn);
+    if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out) % 16 != 0)
+        return fail(ASTRAEA_ERR_INVALID, "%s: q, k, v and the output must be 16-byte aligned", fn);
     if (((uintptr_t)idx_sel | (uintptr_t)lse_sel) % 4 != 0)
         return fail(ASTRAEA_ERR_INVALID, "%s: idx_sel / lse_sel must be 4-byte aligned", fn);
     if (q_stride_h < D || kv_stride_h < D || q_stride_n < D || kv_stride_n < D)
@@ -110,9 +115,32 @@ int astraea_sparse_attn_fwd(const void *q, const void *k, const void *v, astraea
         return fail(ASTRAEA_ERR_WORKSPACE, "%s: workspace must be 256-byte aligned and >= %zu bytes", fn, need);
     if (dt == ASTRAEA_BF16)
         return launch_attn_bf16_d128(q, k, v, N, H, q_stride_n, q_stride_h, kv_stride_n, kv_stride_h, idx_sel, k_sel,
-                                     q_is_compact, softmax_scale, o_sel, lse_sel, workspace, (hipStream_t)stream);
+                                     q_is_compact, softmax_scale, out, out_stride_n, scatter, lse_sel, workspace,
+                                     (hipStream_t)stream);
     return launch_attn_f32(q, k, v, N, H, D, q_stride_n, q_stride_h, kv_stride_n, kv_stride_h, idx_sel, k_sel,
-                           q_is_compact, softmax_scale, o_sel, lse_sel, (hipStream_t)stream);
+                           q_is_compact, softmax_scale, out, out_stride_n, scatter, lse_sel, (hipStream_t)stream);
+}
+
+int astraea_sparse_attn_fwd(const void *q, const void *k, const void *v, astraea_dtype dt, int64_t N, int32_t H,
+                            int32_t D, int64_t q_stride_n, int64_t q_stride_h, int64_t kv_stride_n,
+                            int64_t kv_stride_h, const int32_t *idx_sel, int64_t k_sel, int q_is_compact,
+                            float softmax_scale, void *o_sel, float *lse_sel, void *workspace,
+                            size_t workspace_bytes, void *stream)
+{
+    return sparse_attn_common("astraea_sparse_attn_fwd", q, k, v, dt, N, H, D, q_stride_n, q_stride_h, kv_stride_n,
+                              kv_stride_h, idx_sel, k_sel, q_is_compact, softmax_scale, o_sel, (int64_t)H * D, 0,
+                              lse_sel, workspace, workspace_bytes, stream);
+}
+
+int astraea_sparse_attn_update_fwd(const void *q, const void *k, const void *v, astraea_dtype dt, int64_t N, int32_t H,
+                                   int32_t D, int64_t q_stride_n, int64_t q_stride_h, int64_t kv_stride_n,
+                                   int64_t kv_stride_h, const int32_t *idx_sel, int64_t k_sel, int q_is_compact,
+                                   float softmax_scale, void *out_cache, int64_t cache_row_stride, float *lse_sel,
+                                   void *workspace, size_t workspace_bytes, void *stream)
+{
+    return sparse_attn_common("astraea_sparse_attn_update_fwd", q, k, v, dt, N, H, D, q_stride_n, q_stride_h,
+                              kv_stride_n, kv_stride_h, idx_sel, k_sel, q_is_compact, softmax_scale, out_cache,
+                              cache_row_stride, 1, lse_sel, workspace, workspace_bytes, stream);
 }
 
 static int check_rows(const char *fn, const void *a, const void *b, astraea_dtype dt, int64_t N, int64_t row_elems,

@@ -164,7 +164,8 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
     const __bf16 *__restrict__ q, const __bf16 *__restrict__ k, const char *__restrict__ vt, int64_t N, int32_t H,
     int64_t q_stride_n, int64_t q_stride_h, int64_t kv_stride_n, int64_t kv_stride_h,
     const int32_t *__restrict__ idx_sel, int64_t k_sel, int q_is_compact, float scale_log2e,
-    __bf16 *__restrict__ o_sel, float *__restrict__ lse_sel, AttnSchedule sch, float *__restrict__ partial)
+    __bf16 *__restrict__ o_sel, int64_t o_stride_n, int o_scatter, float *__restrict__ lse_sel, AttnSchedule sch,
+    float *__restrict__ partial)
 {
     // [parity][K tile | V^T tile]; 64 KiB, one 8-wave workgroup per CU (two waves per SIMD)
     __shared__ __attribute__((aligned(1024))) char lds[2 * kBufBytes];
@@ -461,7 +462,9 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
     const float inv = 1.0f / l_tot;
     const int64_t rr = r0 + qc;
     if (rr >= k_sel) return;
-    __bf16 *op = o_sel + (rr * H + head) * (int64_t)D;
+    // compact output row rr, or straight into the cached buffer's row of that token
+    const int64_t orow = o_scatter ? (int64_t)idx_sel[rr] : rr;
+    __bf16 *op = o_sel + orow * o_stride_n + (int64_t)head * D;
 #pragma unroll
     for (int b = 0; b < 4; ++b)
 #pragma unroll
@@ -480,7 +483,8 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
 // O = sum_s w_s O_s / sum_s w_s l_s.  Workgroup (x, y) handles rows 8*y .. 8*y+7 of split item x; a
 // thread handles one row and four head-dim elements.
 __global__ __launch_bounds__(256) void merge_partials_kernel(const float *__restrict__ partial, AttnSchedule sch,
-                                                             int32_t H, int64_t k_sel, __bf16 *__restrict__ o_sel,
+                                                             int32_t H, int64_t k_sel, const int32_t *__restrict__ idx_sel,
+                                                             __bf16 *__restrict__ o_sel, int64_t o_stride_n, int o_scatter,
                                                              float *__restrict__ lse_sel)
 {
     const int64_t left = sch.items_per_xcd - sch.full_items;
@@ -513,7 +517,8 @@ __global__ __launch_bounds__(256) void merge_partials_kernel(const float *__rest
         uint2v o4;
         o4[0] = pack_bf16(acc.x * inv, acc.y * inv);
         o4[1] = pack_bf16(acc.z * inv, acc.w * inv);
-        *reinterpret_cast<uint2v *>(o_sel + (rr * H + head) * (int64_t)D + d4) = o4;
+        const int64_t orow = o_scatter ? (int64_t)idx_sel[rr] : rr;
+        *reinterpret_cast<uint2v *>(o_sel + orow * o_stride_n + (int64_t)head * D + d4) = o4;
         if (lse_sel && d4 == 0) lse_sel[rr * H + head] = (m_star + log2f(l)) * 0.69314718055994530942f;
     }
 }
@@ -535,7 +540,8 @@ size_t attn_bf16_workspace_bytes(int64_t N, int32_t H)
 
 int launch_attn_bf16_d128(const void *q, const void *k, const void *v, int64_t N, int32_t H, int64_t q_stride_n,
                           int64_t q_stride_h, int64_t kv_stride_n, int64_t kv_stride_h, const int32_t *idx_sel,
-                          int64_t k_sel, int q_is_compact, float scale, void *o_sel, float *lse_sel, void *workspace,
+                          int64_t k_sel, int q_is_compact, float scale, void *o_sel, int64_t o_stride_n, int o_scatter,
+                          float *lse_sel, void *workspace,
                           hipStream_t stream)
 {
     if (k_sel == 0) return ASTRAEA_OK;
@@ -581,10 +587,11 @@ int launch_attn_bf16_d128(const void *q, const void *k, const void *v, int64_t N
     dim3 grid((unsigned)(slots * kNumXcd)), block(kWaves * kWave);
     hipLaunchKernelGGL(attn_bf16_kernel, grid, block, 0, stream, (const __bf16 *)q, (const __bf16 *)k,
                        (const char *)vt, N, H, q_stride_n, q_stride_h, kv_stride_n, kv_stride_h, idx_sel, k_sel,
-                       q_is_compact, scale * 1.44269504088896340736f, (__bf16 *)o_sel, lse_sel, sch, partial);
+                       q_is_compact, scale * 1.44269504088896340736f, (__bf16 *)o_sel, o_stride_n, o_scatter, lse_sel, sch,
+                       partial);
     if (left > 0)
         hipLaunchKernelGGL(merge_partials_kernel, dim3((unsigned)(left * kNumXcd), kBq / 8), dim3(256), 0, stream, partial, sch,
-                           H, k_sel, (__bf16 *)o_sel, lse_sel);
+                           H, k_sel, idx_sel, (__bf16 *)o_sel, o_stride_n, o_scatter, lse_sel);
     return check_launch("astraea_sparse_attn_fwd(bf16)");
 }
 

@@ -34,7 +34,7 @@ __global__ __launch_bounds__(kWaves *kWave) void attn_f32_kernel(
     const float *__restrict__ q, const float *__restrict__ k, const float *__restrict__ v, int64_t N, int32_t H,
     int64_t q_stride_n, int64_t q_stride_h, int64_t kv_stride_n, int64_t kv_stride_h,
     const int32_t *__restrict__ idx_sel, int64_t k_sel, int q_is_compact, float scale_log2e,
-    float *__restrict__ o_sel, float *__restrict__ lse_sel)
+    float *__restrict__ o_sel, int64_t o_stride_n, int o_scatter, float *__restrict__ lse_sel)
 {
     constexpr int KP = D + 2;      // K tile pitch (floats): lanes (key, d-parity) hit 64 distinct banks
     constexpr int VP = D + 8;      // V tile pitch: rows r and r+4 land 32 banks apart
@@ -134,7 +134,9 @@ __global__ __launch_bounds__(kWaves *kWave) void attn_f32_kernel(
     const float inv = 1.0f / l_tot;
     const int64_t rr = r0 + qc;
     if (rr >= k_sel) return;
-    float *op = o_sel + (rr * H + head) * (int64_t)D;
+    // compact output row rr, or straight into the cached buffer's row of that token
+    const int64_t orow = o_scatter ? (int64_t)idx_sel[rr] : rr;
+    float *op = o_sel + orow * o_stride_n + (int64_t)head * D;
 #pragma unroll
     for (int b = 0; b < DB; ++b)
 #pragma unroll
@@ -151,7 +153,8 @@ __global__ __launch_bounds__(kWaves *kWave) void attn_f32_kernel(
 
 int launch_attn_f32(const void *q, const void *k, const void *v, int64_t N, int32_t H, int32_t D, int64_t q_stride_n,
                     int64_t q_stride_h, int64_t kv_stride_n, int64_t kv_stride_h, const int32_t *idx_sel,
-                    int64_t k_sel, int q_is_compact, float scale, void *o_sel, float *lse_sel, hipStream_t stream)
+                    int64_t k_sel, int q_is_compact, float scale, void *o_sel, int64_t o_stride_n, int o_scatter,
+                    float *lse_sel, hipStream_t stream)
 {
     if (k_sel == 0) return ASTRAEA_OK;
     dim3 grid((unsigned)((k_sel + kBq - 1) / kBq), (unsigned)H), block(kWaves * kWave);
@@ -159,11 +162,11 @@ int launch_attn_f32(const void *q, const void *k, const void *v, int64_t N, int3
     if (D == 64)
         hipLaunchKernelGGL(attn_f32_kernel<64>, grid, block, 0, stream, (const float *)q, (const float *)k,
                            (const float *)v, N, H, q_stride_n, q_stride_h, kv_stride_n, kv_stride_h, idx_sel, k_sel,
-                           q_is_compact, c, (float *)o_sel, lse_sel);
+                           q_is_compact, c, (float *)o_sel, o_stride_n, o_scatter, lse_sel);
     else
         hipLaunchKernelGGL(attn_f32_kernel<128>, grid, block, 0, stream, (const float *)q, (const float *)k,
                            (const float *)v, N, H, q_stride_n, q_stride_h, kv_stride_n, kv_stride_h, idx_sel, k_sel,
-                           q_is_compact, c, (float *)o_sel, lse_sel);
+                           q_is_compact, c, (float *)o_sel, o_stride_n, o_scatter, lse_sel);
     return check_launch("astraea_sparse_attn_fwd(f32)");
 }
 

@@ -35,10 +35,12 @@ int launch_lse_weight_update(const float *lse_sel, int32_t H, int64_t N, const i
 size_t attn_bf16_workspace_bytes(int64_t N, int32_t H);
 int launch_attn_bf16_d128(const void *q, const void *k, const void *v, int64_t N, int32_t H, int64_t q_stride_n,
                           int64_t q_stride_h, int64_t kv_stride_n, int64_t kv_stride_h, const int32_t *idx_sel,
-                          int64_t k_sel, int q_is_compact, float scale, void *o_sel, float *lse_sel, void *workspace,
+                          int64_t k_sel, int q_is_compact, float scale, void *o_sel, int64_t o_stride_n, int o_scatter,
+                          float *lse_sel, void *workspace,
                           hipStream_t stream);
 int launch_attn_f32(const void *q, const void *k, const void *v, int64_t N, int32_t H, int32_t D, int64_t q_stride_n,
                     int64_t q_stride_h, int64_t kv_stride_n, int64_t kv_stride_h, const int32_t *idx_sel,
-                    int64_t k_sel, int q_is_compact, float scale, void *o_sel, float *lse_sel, hipStream_t stream);
+                    int64_t k_sel, int q_is_compact, float scale, void *o_sel, int64_t o_stride_n, int o_scatter,
+                    float *lse_sel, hipStream_t stream);
 
 }  // namespace astraea

@@ -21,8 +21,11 @@ from . import binding as ab
 class LayerStep:
     """Pre-allocated buffers plus the call chain for one (N, H, D) layer."""
 
-    def __init__(self, N: int, H: int, D: int, dtype: torch.dtype, device="cuda"):
+    def __init__(self, N: int, H: int, D: int, dtype: torch.dtype, device="cuda", fused_update: bool = False):
         self.N, self.H, self.D, self.dtype = N, H, D, dtype
+        # fused_update: the attention writes its rows straight into the cached output buffer
+        # (astraea_sparse_attn_update_fwd) instead of into o_sel followed by a scatter
+        self.fused_update = fused_update
         self.score = torch.empty(N, dtype=torch.float32, device=device)
         self.idx_sel = torch.empty(max(N, 1), dtype=torch.int32, device=device)
         self.o_sel = torch.empty((N, H, D), dtype=dtype, device=device)
@@ -50,6 +53,10 @@ class LayerStep:
         ab.astraea_sparse_attn_fwd(t["q"], t["k_cache"], t["v_cache"], self.idx_sel, k, self.o_sel[:max(k, 1)],
                                    self.scale, q_is_compact=False, lse_sel=lse, workspace=self.attn_ws)
 
+    def step_attn_update(self, t: Dict[str, torch.Tensor], k: int, lse: Optional[torch.Tensor] = None) -> None:
+        ab.astraea_sparse_attn_update_fwd(t["q"], t["k_cache"], t["v_cache"], self.idx_sel, k, t["out_cache"],
+                                          self.scale, q_is_compact=False, lse_sel=lse, workspace=self.attn_ws)
+
     def step_scatter(self, t: Dict[str, torch.Tensor], k: int) -> None:
         E = self.H * self.D
         ab.astraea_scatter_update(t["out_cache"], self.o_sel.view(self.N, E), self.idx_sel, k, src_is_full=False)
@@ -59,8 +66,11 @@ class LayerStep:
         self.step_score(t)
         self.step_select(k)
         self.step_kv_refresh(t, k)
-        self.step_attn(t, k)
-        self.step_scatter(t, k)
+        if self.fused_update:
+            self.step_attn_update(t, k)
+        else:
+            self.step_attn(t, k)
+            self.step_scatter(t, k)
 
 
 class StatefulLayer(LayerStep):
@@ -70,8 +80,8 @@ class StatefulLayer(LayerStep):
     non-selections n_i (`skip_count`), whose penalty e^{n_i} comes from a table built by the caller."""
 
     def __init__(self, N: int, H: int, D: int, C: int, dtype: torch.dtype, penalty_table: torch.Tensor,
-                 w_alpha: float = 1.0, w_beta: float = 0.0, device="cuda"):
-        super().__init__(N, H, D, dtype, device)
+                 w_alpha: float = 1.0, w_beta: float = 0.0, device="cuda", fused_update: bool = False):
+        super().__init__(N, H, D, dtype, device, fused_update)
         self.x_ref = torch.zeros((N, C), dtype=dtype, device=device)
         self.lse_weight = torch.ones(N, dtype=torch.float32, device=device)
         self.skip_count = torch.zeros(N, dtype=torch.int32, device=device)
@@ -96,6 +106,10 @@ class StatefulLayer(LayerStep):
         self.step_score(t)
         self.step_select(k)
         self.step_kv_refresh(t, k)
-        self.step_attn(t, k, lse=self.lse_sel[:max(k, 1)])
-        self.step_state(t, k)
-        self.step_scatter(t, k)
+        if self.fused_update:
+            self.step_attn_update(t, k, lse=self.lse_sel[:max(k, 1)])
+            self.step_state(t, k)
+        else:
+            self.step_attn(t, k, lse=self.lse_sel[:max(k, 1)])
+            self.step_state(t, k)
+            self.step_scatter(t, k)

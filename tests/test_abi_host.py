@@ -117,6 +117,24 @@ def test_sparse_attn_rejects_bad_arguments(L):
     assert call(k_sel=0, q=None, k=None, v=None, o=None, idx=None) == ab.OK     # budget 0: nothing to do
 
 
+def test_sparse_attn_update_rejects_bad_arguments(L):
+    f = L.astraea_sparse_attn_update_fwd
+
+    def call(dt=ab.BF16, N=100, H=2, D=128, idx=FAKE, k_sel=10, compact=0, scale=0.1, q=FAKE, out=FAKE, stride=256):
+        return f(q, FAKE, FAKE, dt, N, H, D, 256, 128, 256, 128, idx, k_sel, compact, scale, out, stride, None, None, 0,
+                 None)
+
+    assert call(stride=248) == ab.ERR_INVALID                   # narrower than H*D
+    assert call(stride=260) == ab.ERR_INVALID                   # rows must stay 16-byte aligned
+    assert call(idx=None, compact=1) == ab.ERR_INVALID          # the index list also says where rows go
+    assert call(k_sel=101, compact=1) == ab.ERR_INVALID         # cannot place more rows than there are tokens
+    assert call(out=None) == ab.ERR_INVALID
+    assert call(out=FAKE + 8) == ab.ERR_INVALID
+    assert call(dt=ab.F32, D=96) == ab.ERR_UNSUPPORTED
+    assert call() == ab.ERR_WORKSPACE                           # everything else valid: the bf16 path wants its workspace
+    assert call(k_sel=0, q=None, out=None, idx=None) == ab.OK   # budget 0 leaves the cache as it is
+
+
 def test_row_movers_reject_bad_arguments(L):
     sc, ga = L.astraea_scatter_update, L.astraea_gather_rows
     assert sc(FAKE, FAKE, 5, 10, 8, 8, 8, FAKE, 3, 0, None) == ab.ERR_UNSUPPORTED

@@ -63,7 +63,8 @@ def _check_step(w, t, host, layer, budget_pct, n_rows, tag, out_known=None):
     assert np.array_equal(got[rem_known], host["out_cache"][rem_known]), f"{tag}: unselected cache rows changed"
     assert np.array_equal(got[e_rem], before[e_rem]), f"{tag}: a row outside the selection moved"
     # scatter positions: cache row idx[r] holds exactly row r of the compact attention output
-    assert np.array_equal(got[e_idx], to_np(layer.o_sel[:k]).reshape(k, E)), f"{tag}: scatter positions"
+    if not layer.fused_update:      # the fused path has no compact result to compare positions with
+        assert np.array_equal(got[e_idx], to_np(layer.o_sel[:k]).reshape(k, E)), f"{tag}: scatter positions"
 
     # attention on the sampled rows against the oracle
     rows = np.arange(k) if n_rows >= k else _sample_rows(k, n_rows, seed=n + k)
@@ -102,18 +103,20 @@ def test_config1_bf16_key_bias(budget):
     _check_step(w, t, _host(t), layer, budget, n_rows=48, tag=f"cfg1@{budget}%")
 
 
-def test_config2_480p():
+@pytest.mark.parametrize("fused", [False, True])
+def test_config2_480p(fused):
     w = synth.WORKLOADS["cfg2"]
     t = synth.make_layer_inputs(w, seed=0, device=DEV)
-    layer = LayerStep(w.N, w.H, w.D, w.torch_dtype, device=DEV)
-    _check_step(w, t, _host(t), layer, 40, n_rows=48, tag="cfg2")
+    layer = LayerStep(w.N, w.H, w.D, w.torch_dtype, device=DEV, fused_update=fused)
+    _check_step(w, t, _host(t), layer, 40, n_rows=48, tag="cfg2" + ("/fused" if fused else ""))
 
 
-def test_config3_720p_headline():
+@pytest.mark.parametrize("fused", [False, True])
+def test_config3_720p_headline(fused):
     w = synth.WORKLOADS["cfg3"]
     t = synth.make_layer_inputs(w, seed=0, device=DEV)
-    layer = LayerStep(w.N, w.H, w.D, w.torch_dtype, device=DEV)
-    _check_step(w, t, _host(t), layer, 30, n_rows=24, tag="cfg3")
+    layer = LayerStep(w.N, w.H, w.D, w.torch_dtype, device=DEV, fused_update=fused)
+    _check_step(w, t, _host(t), layer, 30, n_rows=24, tag="cfg3" + ("/fused" if fused else ""))
 
 
 def test_config4_sweep_three_steps_with_carried_caches():

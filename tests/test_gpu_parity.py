@@ -313,3 +313,45 @@ def test_attn_bf16_split_items_match_oracle(n, h, k_sel):
     # determinism: the same call twice gives the same bits
     o2, _ = _run_attn(q, k, v, idx, scale)
     assert np.array_equal(o, o2)
+
+
+# ------------------------------------------- attention fused with the cache update --
+
+@pytest.mark.parametrize("dtype,n,h,d,k_sel,pad", [
+    (torch.bfloat16, 1000, 3, 128, 333, 0), (torch.bfloat16, 4100, 24, 128, 1100, 0),   # second shape has split items
+    (torch.bfloat16, 700, 2, 128, 700, 64), (torch.float32, 300, 2, 64, 77, 0), (torch.float32, 515, 3, 128, 130, 8)])
+def test_attn_update_equals_attention_then_scatter(dtype, n, h, d, k_sel, pad):
+    """astraea_sparse_attn_update_fwd == astraea_sparse_attn_fwd + astraea_scatter_update, bit for bit, and rows
+    outside idx_sel (and the padding columns of a wider cache row) keep their bits."""
+    q, k, v, idx = _attn_case(n, h, d, k_sel, dtype, seed=3 * n + h)
+    scale = 1.0 / math.sqrt(d)
+    g = torch.Generator().manual_seed(n)
+    e = h * d
+    cache0 = torch.randn(n, e + pad, generator=g).to(dtype)
+    wsb = ab.workspace_bytes(ab.OP_SPARSE_ATTN, n, k_sel, h, d)
+    ws = torch.empty(max(wsb, 1), dtype=torch.uint8, device=DEV) if wsb else None
+    dq, dk, dv, didx = q.to(DEV), k.to(DEV), v.to(DEV), idx.to(DEV)
+    # two steps
+    o = torch.empty(k_sel, h, d, dtype=dtype, device=DEV)
+    lse_a = torch.empty(k_sel, h, device=DEV)
+    ab.astraea_sparse_attn_fwd(dq, dk, dv, didx, k_sel, o, scale, lse_sel=lse_a, workspace=ws)
+    cache_a = cache0.to(DEV)
+    ab.astraea_scatter_update(cache_a[:, :e], o.view(k_sel, e), didx, k_sel, src_is_full=False)
+    # one step
+    cache_b = cache0.to(DEV)
+    lse_b = torch.empty(k_sel, h, device=DEV)
+    ab.astraea_sparse_attn_update_fwd(dq, dk, dv, didx, k_sel, cache_b[:, :e], scale, lse_sel=lse_b, workspace=ws)
+    _sync()
+    a, b = to_np(cache_a), to_np(cache_b)
+    assert np.array_equal(a, b)
+    assert np.array_equal(lse_a.cpu().numpy(), lse_b.cpu().numpy())
+    rest = np.setdiff1d(np.arange(n), idx.numpy())
+    assert np.array_equal(b[rest], to_np(cache0)[rest])
+    assert np.array_equal(b[:, e:], to_np(cache0)[:, e:])
+    # and against the oracle on the selected rows
+    eo, _ = oracle.sparse_attn(to_np(q), to_np(k), to_np(v), idx.numpy(), scale)
+    got = as_f64(b[idx.numpy()][:, :e]).reshape(k_sel, h, d)
+    if dtype == torch.float32:
+        assert np.max(np.abs(got - eo)) <= 1e-4
+    else:
+        assert _rel_l2(got, eo) <= 1e-2
