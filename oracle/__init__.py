@@ -19,6 +19,7 @@ _LIB = _HERE / "liboracle.so"
 
 F32, BF16 = 0, 1
 DELTA_L2, DELTA_MEAN_ABS, DELTA_MEAN_SQ = 0, 1, 2
+ACT_NONE, ACT_GELU_TANH = 0, 1
 
 
 def build(force: bool = False) -> Path:
@@ -50,6 +51,7 @@ def lib() -> C.CDLL:
         L.oracle_round_to_dtype.argtypes = [vp, i64, C.c_int, vp]
         L.oracle_scatter.argtypes = [vp, vp, C.c_int, i64, i64, i64, i64, vp, i64, C.c_int]
         L.oracle_gather.argtypes = [vp, vp, C.c_int, i64, i64, i64, i64, vp, i64]
+        L.oracle_sparse_linear.argtypes = [vp, C.c_int, i64, i64, i64, vp, i64, vp, C.c_int, vp, i64, C.c_int, vp]
         L.oracle_budget_to_k.argtypes = [i64, i32]
         L.oracle_budget_to_k.restype = i64
         _lib = L
@@ -184,6 +186,27 @@ def gather(src: np.ndarray, idx_sel) -> np.ndarray:
     _check(lib().oracle_gather(_ptr(src), _ptr(dst), _dtype_code(src), n, e, e, e, _ptr(idx), idx.shape[0]),
            "oracle_gather")
     return dst
+
+
+def sparse_linear(x: np.ndarray, w: np.ndarray, idx_sel, bias=None, act: int = ACT_NONE,
+                  x_is_compact: bool = False) -> np.ndarray:
+    """x: [N or k_sel, c_in]; w: [c_out, c_in]; returns act(x[idx] @ w.T + bias) as [k_sel, c_out] fp64."""
+    x, w = np.ascontiguousarray(x), np.ascontiguousarray(w)
+    assert x.ndim == 2 and w.ndim == 2 and x.shape[1] == w.shape[1] and x.dtype == w.dtype
+    if bias is not None:
+        bias = np.ascontiguousarray(bias)
+        assert bias.dtype == x.dtype and bias.shape == (w.shape[0],)
+    if idx_sel is None:
+        assert x_is_compact
+        idx, k_sel = None, x.shape[0]
+    else:
+        idx = np.ascontiguousarray(idx_sel, dtype=np.int32)
+        k_sel = idx.shape[0]
+    y = np.empty((k_sel, w.shape[0]), dtype=np.float64)
+    _check(lib().oracle_sparse_linear(_ptr(x), _dtype_code(x), x.shape[0], x.shape[1], x.shape[1], _ptr(w), w.shape[0],
+                                      _ptr(bias), act, _ptr(idx), k_sel, 1 if x_is_compact else 0, _ptr(y)),
+           "oracle_sparse_linear")
+    return y
 
 
 def budget_to_k(n: int, pct: int) -> int:

@@ -13,6 +13,9 @@
  *   oracle_scatter      X_out,t[I_sel] <- fresh rows, X_out,t[I_remain] kept (Algorithm 1, cache reuse step)
  *   oracle_gather       X[I_sel]                                             (Algorithm 1, query selection)
  *   oracle_lse_weight_update  per-token S_LSE carried to the next step          (selection metric, S_sig equation)
+ *   oracle_sparse_linear  act(X[I_sel] W^T + b): the per-token layers on the selected rows only
+ *                                                                             (Algorithm 1, "Q = X_in[I_sel] W_Q";
+ *                                                                             FLOPs appendix: projections and MLP)
  *
  * Precision.  Attention accumulates in fp64 (acc_mode 0) or in fp32 (acc_mode 1,
  * the "naive fp32" form); its outputs are returned as fp64.  The score is a
@@ -425,6 +428,45 @@ int oracle_gather(const void *src, void *dst, int dtype, int64_t N, int64_t row_
             return -1;
         memcpy((char *)dst + (size_t)(r * dst_row_stride) * es, (const char *)src + (size_t)(i * src_row_stride) * es,
                (size_t)row_elems * es);
+    }
+    return 0;
+}
+
+/*
+ * Per-token linear layer evaluated for the selected tokens only (Algorithm 1: Q = X_in[I_sel] W_Q, and in the
+ * same way every projection and MLP layer of the block, which act on each token by itself; FLOPs appendix,
+ * the 2*N*D*D' terms with N replaced by the number of selected tokens):
+ *     y[r, o] = act( sum_c x[row(r), c] * w[o, c] + bias[o] ),   row(r) = idx_sel[r], or r if x_is_compact
+ * w is [c_out, c_in] (one output feature's weights contiguous), bias may be NULL, everything in fp64.
+ * act 0: identity; act 1: GELU in its tanh form, 0.5 t (1 + tanh( sqrt(2/pi) (t + 0.044715 t^3) )).
+ * (The paper does not name the MLP's activation; this is the one the video DiTs it evaluates use.)
+ */
+enum { ORACLE_ACT_NONE = 0, ORACLE_ACT_GELU_TANH = 1 };
+int oracle_sparse_linear(const void *x, int dtype, int64_t N, int64_t c_in, int64_t x_row_stride, const void *w,
+                         int64_t c_out, const void *bias, int act, const int32_t *idx_sel, int64_t k_sel,
+                         int x_is_compact, double *y)
+{
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16)
+        return -1;
+    if (act != ORACLE_ACT_NONE && act != ORACLE_ACT_GELU_TANH)
+        return -1;
+    if (!x_is_compact)
+        for (int64_t r = 0; r < k_sel; ++r)
+            if (idx_sel[r] < 0 || idx_sel[r] >= N)
+                return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < k_sel; ++r) {
+        int64_t row = x_is_compact ? r : (int64_t)idx_sel[r];
+        for (int64_t o = 0; o < c_out; ++o) {
+            double t = 0.0;
+            for (int64_t c = 0; c < c_in; ++c)
+                t += (double)load_elem(x, dtype, row * x_row_stride + c) * (double)load_elem(w, dtype, o * c_in + c);
+            if (bias)
+                t += (double)load_elem(bias, dtype, o);
+            if (act == ORACLE_ACT_GELU_TANH)
+                t = 0.5 * t * (1.0 + tanh(0.79788456080286535588 * (t + 0.044715 * t * t * t)));
+            y[r * c_out + o] = t;
+        }
     }
     return 0;
 }

@@ -10,6 +10,7 @@ import math
 import numpy as np
 import pytest
 import torch
+import torch.nn.functional as F
 
 import oracle
 from conftest import bf16_bits_to_f64, to_np
@@ -390,3 +391,69 @@ def test_paper_flops_ratio_is_the_budget():
         orig = float(orig)
         for pct, val in ((40, b40), (50, b50), (70, b70)):
             assert abs(float(val) / orig - pct / 100.0) < 2e-4, name
+
+
+# ------------------------------------------------- per-token layers on selected rows --
+
+def _bf16(t):
+    return t.bfloat16().view(torch.int16).numpy().view(np.uint16)
+
+
+def test_sparse_linear_equals_library_linear_and_gelu():
+    """Special case that is a library routine: gather, torch linear in fp64, torch GELU(tanh)."""
+    g = torch.Generator().manual_seed(5)
+    n, cin, cout, k = 50, 24, 17, 20
+    x, w, b = torch.randn(n, cin, generator=g), torch.randn(cout, cin, generator=g), torch.randn(cout, generator=g)
+    idx = torch.randperm(n, generator=g)[:k].sort().values
+    for act, fn in ((oracle.ACT_NONE, lambda t: t), (oracle.ACT_GELU_TANH, lambda t: F.gelu(t, approximate="tanh"))):
+        ref = fn(F.linear(x[idx].double(), w.double(), b.double())).numpy()
+        got = oracle.sparse_linear(x.numpy(), w.numpy(), idx.numpy(), bias=b.numpy(), act=act)
+        assert np.max(np.abs(got - ref)) < 1e-12
+    # bf16 inputs are taken at their stored values
+    xb, wb = x.bfloat16(), w.bfloat16()
+    ref = F.linear(xb[idx].double(), wb.double()).numpy()
+    got = oracle.sparse_linear(_bf16(x), _bf16(w), idx.numpy())
+    assert np.max(np.abs(got - ref)) < 1e-12
+
+
+def test_sparse_linear_closed_forms():
+    n, c = 9, 6
+    x = np.arange(n * c, dtype=np.float32).reshape(n, c) - 20.0
+    idx = np.array([1, 4, 8], np.int32)
+    eye = np.eye(c, dtype=np.float32)
+    assert np.array_equal(oracle.sparse_linear(x, eye, idx), x[idx].astype(np.float64))          # identity = gather
+    assert np.array_equal(oracle.sparse_linear(x[idx], eye, None, x_is_compact=True), x[idx])     # compact input
+    # a weight row that is a unit vector picks a column: catches a transposed weight
+    w = np.zeros((2, c), np.float32)
+    w[0, 5], w[1, 2] = 1.0, -2.0
+    y = oracle.sparse_linear(x, w, idx)
+    assert np.array_equal(y[:, 0], x[idx, 5]) and np.array_equal(y[:, 1], -2.0 * x[idx, 2])
+    # x = 0: the output is act(bias) for every row; GELU fixed points and limits
+    b = np.array([0.0, 30.0, -30.0, 1.0], np.float32)
+    y = oracle.sparse_linear(np.zeros((n, c), np.float32), np.zeros((4, c), np.float32), idx, bias=b,
+                             act=oracle.ACT_GELU_TANH)
+    assert np.all(y[:, 0] == 0.0) and np.all(y[:, 1] == 30.0) and np.all(np.abs(y[:, 2]) < 1e-300)
+    assert np.allclose(y[:, 3], 0.8411919906082768, atol=1e-15)      # 0.5 (1 + tanh(sqrt(2/pi) * 1.044715))
+    assert y.shape == (3, 4) and np.all(y == y[0])
+
+
+def test_sparse_linear_brute_force_and_linearity():
+    g = np.random.default_rng(2)
+    n, cin, cout = 7, 5, 4
+    x, x2 = g.standard_normal((n, cin)).astype(np.float32), g.standard_normal((n, cin)).astype(np.float32)
+    w, b = g.standard_normal((cout, cin)).astype(np.float32), g.standard_normal(cout).astype(np.float32)
+    idx = np.array([6, 0, 3], np.int32)
+    y = oracle.sparse_linear(x, w, idx, bias=b)
+    for r, i in enumerate(idx):
+        for o in range(cout):
+            t = float(b[o])
+            for c_ in range(cin):
+                t += float(x[i, c_]) * float(w[o, c_])
+            assert abs(y[r, o] - t) < 1e-13
+    # without activation and bias the layer is linear in x
+    s = (x.astype(np.float64) + x2.astype(np.float64)).astype(np.float32)
+    exact = np.array_equal(s.astype(np.float64), x.astype(np.float64) + x2.astype(np.float64))
+    ya, yb, ys = (oracle.sparse_linear(a, w, idx) for a in (x, x2, s))
+    assert np.max(np.abs(ya + yb - ys)) < (1e-13 if exact else 1e-5)
+    # k_sel = 0
+    assert oracle.sparse_linear(x, w, np.zeros(0, np.int32)).shape == (0, cout)
