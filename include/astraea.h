@@ -51,6 +51,7 @@ enum {
 };
 
 /* Operation ids for astraea_workspace_bytes. */
+typedef enum { ASTRAEA_ACT_NONE = 0, ASTRAEA_ACT_GELU_TANH = 1 } astraea_activation;
 enum { ASTRAEA_OP_SELECT_TOPK = 1, ASTRAEA_OP_SPARSE_ATTN = 2 };
 
 /*
@@ -156,6 +157,32 @@ int astraea_sparse_attn_update_fwd(const void *q, const void *k, const void *v, 
 int astraea_scatter_update(void *cache, const void *src, astraea_dtype dt, int64_t N, int64_t row_elems,
                            int64_t cache_row_stride, int64_t src_row_stride, const int32_t *idx_sel,
                            int64_t k_sel, int src_is_full, void *stream);
+
+/*
+ * astraea_sparse_linear - a layer that acts on each token by itself, evaluated for the selected
+ * tokens only (Algorithm 1: Q = X_in[I_sel] W_Q; Sec. 3.2: such layers are computed for the selected
+ * tokens and taken from the cache for the rest; FLOPs appendix: the projection and MLP terms, whose
+ * cost 2*N*c_in*c_out becomes 2*k_sel*c_in*c_out):
+ *     y[row_out(r), o] = act( sum_c x[row_in(r), c] * w[o, c] + bias[o] ),   r = 0..k_sel-1, o = 0..c_out-1
+ *   x        x_is_compact == 0: [N, x_row_stride], row_in(r) = idx_sel[r] (gathered inside the kernel);
+ *            x_is_compact == 1: [k_sel, x_row_stride], row_in(r) = r.
+ *   w        [c_out, c_in] contiguous: the weights of one output feature are contiguous.
+ *   bias     [c_out] or NULL.
+ *   y        y_is_compact == 1: [k_sel, y_row_stride], row_out(r) = r;
+ *            y_is_compact == 0: [N, y_row_stride], row_out(r) = idx_sel[r] and every other row keeps
+ *            what it held: with a cached K, V or output buffer as y this is the projection fused
+ *            with the cache refresh.
+ *   act      ASTRAEA_ACT_NONE, or ASTRAEA_ACT_GELU_TANH: 0.5 t (1 + tanh(sqrt(2/pi) (t + 0.044715 t^3))).
+ * Supported: BF16 (bf16 MFMA, fp32 accumulation, bias and activation in fp32, one rounding to bf16);
+ * c_in a multiple of 64, c_out a multiple of 8, strides multiples of 8 elements, pointers 16-byte
+ * aligned, x and w each spanning less than 4 GiB.  F32 returns ASTRAEA_ERR_UNSUPPORTED.
+ * idx_sel (distinct, in [0, N)) is required unless both sides are compact.  No workspace.
+ * k_sel == 0 enqueues nothing.
+ */
+int astraea_sparse_linear(const void *x, const void *w, const void *bias, astraea_dtype dt, int64_t N, int64_t c_in,
+                          int64_t c_out, int64_t x_row_stride, const int32_t *idx_sel, int64_t k_sel,
+                          int x_is_compact, astraea_activation act, void *y, int64_t y_row_stride, int y_is_compact,
+                          void *stream);
 
 /*
  * astraea_lse_weight_update - carries the softmax by-product S_LSE of the selection metric to the

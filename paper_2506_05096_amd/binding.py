@@ -21,10 +21,11 @@ F32, BF16 = 0, 1
 DELTA_L2, DELTA_MEAN_ABS, DELTA_MEAN_SQ = 0, 1, 2
 OK, ERR_INVALID, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
 OP_SELECT_TOPK, OP_SPARSE_ATTN = 1, 2
+ACT_NONE, ACT_GELU_TANH = 0, 1
 
 EXPORTS = (
     "astraea_score", "astraea_select_topk", "astraea_sparse_attn_fwd", "astraea_sparse_attn_update_fwd",
-    "astraea_scatter_update", "astraea_gather_rows", "astraea_workspace_bytes", "astraea_budget_to_k", "astraea_attn_flops",
+    "astraea_scatter_update", "astraea_gather_rows", "astraea_sparse_linear", "astraea_workspace_bytes", "astraea_budget_to_k", "astraea_attn_flops",
     "astraea_probe_mfma_bf16", "astraea_probe_copy", "astraea_lse_weight_update",
     "astraea_status_string", "astraea_last_error",
 )
@@ -56,6 +57,9 @@ def lib() -> C.CDLL:
                                                      C.c_int, f32, vp, i64, vp, vp, sz, vp]
         L.astraea_scatter_update.argtypes = [vp, vp, C.c_int, i64, i64, i64, i64, vp, i64, C.c_int, vp]
         L.astraea_gather_rows.argtypes = [vp, vp, C.c_int, i64, i64, i64, i64, vp, i64, vp]
+        L.astraea_sparse_linear.argtypes = [vp, vp, vp, C.c_int, i64, i64, i64, i64, vp, i64, C.c_int, C.c_int, vp, i64,
+                                            C.c_int, vp]
+        L.astraea_sparse_linear.restype = C.c_int
         L.astraea_workspace_bytes.argtypes = [C.c_int, i64, i64, i32, i32]
         L.astraea_workspace_bytes.restype = sz
         L.astraea_budget_to_k.argtypes = [i64, i32]
@@ -172,6 +176,21 @@ def astraea_gather_rows(src: torch.Tensor, dst: torch.Tensor, idx_sel: torch.Ten
     assert src.dtype == dst.dtype and src.shape[1] == dst.shape[1]
     _check(lib().astraea_gather_rows(_p(src), _p(dst), _dt(src), src.shape[0], src.shape[1], src.stride(0),
                                      dst.stride(0), _p(idx_sel), k_sel, _stream()))
+
+
+def astraea_sparse_linear(x: torch.Tensor, w: torch.Tensor, bias: Optional[torch.Tensor],
+                          idx_sel: Optional[torch.Tensor], k_sel: int, y: torch.Tensor, act: int = ACT_NONE,
+                          x_is_compact: bool = False, y_is_compact: bool = True, N: Optional[int] = None) -> None:
+    """y[row_out(r)] = act(x[row_in(r)] @ w.T + bias); N is the token count the indices refer to (taken from
+    whichever of x, y is not compact when omitted)."""
+    assert x.dim() == 2 and y.dim() == 2 and w.dim() == 2 and w.is_contiguous()
+    assert x.stride(1) == 1 and y.stride(1) == 1 and x.dtype == w.dtype == y.dtype
+    assert x.shape[1] == w.shape[1] and y.shape[1] == w.shape[0]
+    if N is None:
+        N = x.shape[0] if not x_is_compact else (y.shape[0] if not y_is_compact else max(k_sel, 1))
+    _check(lib().astraea_sparse_linear(_p(x), _p(w), _p(bias), _dt(x), N, w.shape[1], w.shape[0], x.stride(0),
+                                       _p(idx_sel), k_sel, 1 if x_is_compact else 0, act, _p(y), y.stride(0),
+                                       1 if y_is_compact else 0, _stream()))
 
 
 def astraea_lse_weight_update(lse_sel: torch.Tensor, idx_sel: torch.Tensor, k_sel: int, lse_weight: torch.Tensor) -> None:

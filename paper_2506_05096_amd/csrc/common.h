@@ -32,6 +32,10 @@ int launch_move_rows(void *dst, const void *src, int64_t row_bytes, int64_t dst_
 int launch_lse_weight_update(const float *lse_sel, int32_t H, int64_t N, const int32_t *idx_sel, int64_t k_sel,
                              float *lse_weight, hipStream_t stream);
 
+int launch_linear_bf16(const void *x, const void *w, const void *bias, void *y, const int32_t *idx_sel, int64_t k_sel,
+                       int32_t c_in, int32_t c_out, int64_t ldx, int64_t ldy, int x_indexed, int y_indexed, int act,
+                       hipStream_t stream);
+
 size_t attn_bf16_workspace_bytes(int64_t N, int32_t H);
 int launch_attn_bf16_d128(const void *q, const void *k, const void *v, int64_t N, int32_t H, int64_t q_stride_n,
                           int64_t q_stride_h, int64_t kv_stride_n, int64_t kv_stride_h, const int32_t *idx_sel,

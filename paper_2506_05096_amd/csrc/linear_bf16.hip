@@ -1,0 +1,355 @@
+// astraea_sparse_linear, bf16: a per-token linear layer evaluated for the selected tokens only
+// (paper, Algorithm 1: Q = X_in[I_sel] W_Q; Sec. 3.2: every layer that acts on a token by itself is
+// computed for the selected tokens and reused from the cache for the others; FLOPs appendix: the
+// projection and MLP terms):
+//     y[row_out(r), o] = act( sum_c x[row_in(r), c] * w[o, c] + bias[o] )
+// Rows are gathered by index while the input tile is copied into LDS and scattered by index in the
+// epilogue, so neither a compact copy of the input nor one of the output exists.
+//
+// Shape of the computation on gfx950:
+//  * x rows and w rows are both contiguous along the contraction, which is what both operands of
+//    v_mfma_f32_32x32x16_bf16 want (a lane holds 8 consecutive k of one row / column).  w feeds the A
+//    operand and x the B operand, so that an accumulator lane owns one token and 4 consecutive output
+//    features per register group: the epilogue packs them to 8-byte stores along the output row.
+//  * workgroup = 4 waves, one per SIMD, output tile 256 features x 256 tokens, each wave 128 x 128
+//    (4 x 4 MFMA blocks, 256 accumulator registers): one LDS fragment read per two MFMAs.
+//  * the contraction advances in steps of 64; the two 32 KiB tiles of a step go from global memory
+//    straight into LDS (global_load_lds_dwordx4, per-lane addresses, so the row gather costs nothing),
+//    double buffered, 16-byte chunks XOR-swizzled inside each 128-byte row against bank conflicts.
+//    The copy instructions of the next step are spread between the MFMAs of the current one.
+//  * workgroup ids are mapped so that the 32 workgroups resident on one XCD form an 8 x 4 block of
+//    tiles: they stream 8 row tiles and 4 weight tiles through that XCD's L2 instead of 32 + 32.
+#include "common.h"
+
+namespace astraea {
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t uint2v __attribute__((ext_vector_type(2)));
+typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
+
+constexpr int kBm = 256;                 // tokens per tile
+constexpr int kBn = 256;                 // output features per tile
+constexpr int kBk = 64;                  // contraction step
+constexpr int kRowBytes = kBk * 2;       // 128 B of a row per step
+constexpr int kTileBytes = 256 * kRowBytes;          // 32 KiB
+constexpr int kStageBytes = 2 * kTileBytes;          // w tile, then x tile
+constexpr int kNumXcd = 8;
+constexpr int kSbM = 8, kSbN = 4;        // tiles of one XCD round: 8 token tiles x 4 feature tiles
+
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b)
+{
+    floatx2 f = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));   // v_cvt_pk_bf16_f32, RNE
+}
+__device__ __forceinline__ bf16x8 lds_read_b128(uint32_t addr)
+{
+    return *reinterpret_cast<const bf16x8 __attribute__((address_space(3))) *>((uintptr_t)addr);
+}
+// 16 bytes per lane from global memory straight into LDS: lane l lands at lds_wave_base + 16*l.
+__device__ __forceinline__ void dma16(const void *gbase, uint32_t goff, uint32_t lds_wave_base)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_wave_base), "v"(goff), "s"(gbase)
+                 : "memory");
+}
+__device__ __forceinline__ void wait_dma() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// Waits until only the two most recent vector-memory instructions (the L2 warm-up loads) are pending:
+// the counter retires loads in order, so everything issued before them has then landed.
+__device__ __forceinline__ void wait_dma_keep2() { asm volatile("s_waitcnt vmcnt(2)" ::: "memory"); }
+// A 4-byte load whose only purpose is to pull its 128-byte line into L2.  `sink` must stay live until
+// the load has been waited for (the data lands in it whenever it arrives).
+__device__ __forceinline__ void touch_line(const void *gbase, uint32_t goff, uint32_t &sink)
+{
+    asm volatile("global_load_dword %0, %1, %2" : "+v"(sink) : "v"(goff), "s"(gbase) : "memory");
+}
+
+__device__ __forceinline__ float gelu_tanh(float t)
+{
+    // 0.5 t (1 + tanh u) = t / (1 + e^(-2u)),  u = sqrt(2/pi) (t + 0.044715 t^3)
+    const float u = 0.79788456080286535588f * __builtin_fmaf(0.044715f * t, t * t, t);
+    const float e = __builtin_amdgcn_exp2f(-2.0f * 1.44269504088896340736f * u);
+    return t * __builtin_amdgcn_rcpf(1.0f + e);
+}
+
+struct LinearArgs {
+    const __bf16 *x;
+    const __bf16 *w;
+    const __bf16 *bias;        // or null
+    __bf16 *y;
+    const int32_t *idx_sel;    // or null when neither side is indexed
+    int64_t ldx, ldy;          // row strides in elements
+    int32_t k_sel, c_in, c_out;
+    int32_t x_indexed, y_indexed, act;
+    int32_t m_tiles, n_tiles, sb_n;   // tile counts and 4-wide super-block count along the features
+};
+
+__global__ __launch_bounds__(256, 1) void linear_bf16_kernel(LinearArgs a)
+{
+    // [stage][w tile | x tile]; the only LDS object of the kernel, so it starts at LDS address 0, which
+    // the stage flips (XOR) rely on.
+    __shared__ __attribute__((aligned(1024))) char lds[2 * kStageBytes];
+
+    // ---- which tile: workgroup ids reach the XCDs round-robin; each XCD takes every 8th super-block
+    // of 8 x 4 tiles and runs its 32 tiles at the same time.
+    const int xcd = blockIdx.x % kNumXcd, seq = blockIdx.x / kNumXcd;
+    const int sb = (seq / (kSbM * kSbN)) * kNumXcd + xcd, inner = seq % (kSbM * kSbN);
+    const int mt = (sb / a.sb_n) * kSbM + inner % kSbM;
+    const int nt = (sb % a.sb_n) * kSbN + inner / kSbM;
+    if (mt >= a.m_tiles || nt >= a.n_tiles) return;
+    const int m0 = mt * kBm, n0 = nt * kBn;
+
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int qc = lane & 31, hf = lane >> 5;
+    const int wn = wave & 1, wm = wave >> 1;          // this wave's 128-feature and 128-token halves
+    const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
+
+    // ---- tile copies.  One instruction fills 1 KiB = 8 rows of a tile; wave w issues instructions
+    // w, w+4, ..., w+28 of each tile.  Lane l serves row 8*i + l/8 and the physical chunk l%8, which
+    // holds logical chunk (l%8) ^ ((row/2)%8); for the rows of one wave that is the same in all 8
+    // instructions, so a lane's byte offset inside its rows is fixed.
+    const int d_row = lane >> 3;
+    const int lchunk = (lane & 7) ^ ((4 * (wave & 1) + (lane >> 4)) & 7);
+    uint32_t woff[8], xoff[8];           // byte offsets of this lane's rows from w and x
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        const int r = 8 * (wave + 4 * t) + d_row;
+        int n = n0 + r;                  // rows past the end re-read the last one; they are never stored
+        if (n > a.c_out - 1) n = a.c_out - 1;
+        woff[t] = (uint32_t)n * (uint32_t)a.c_in * 2u + (uint32_t)lchunk * 16u;
+        int m = m0 + r;
+        if (m > a.k_sel - 1) m = a.k_sel - 1;
+        const int64_t row = a.x_indexed ? (int64_t)a.idx_sel[m] : (int64_t)m;
+        xoff[t] = (uint32_t)(row * a.ldx * 2) + (uint32_t)lchunk * 16u;
+    }
+    // all index loads must have landed before the loop: a load still pending at the loop header would
+    // make the compiler wait on the vector-memory counter inside it
+#pragma unroll
+    for (int t = 0; t < 8; ++t) asm volatile("" ::"v"(xoff[t]), "v"(woff[t]));
+
+    const char *wg = reinterpret_cast<const char *>(a.w);
+    const char *xg = reinterpret_cast<const char *>(a.x);
+    // L2 warm-up: a step's 128 bytes of one row are one cache line, and this wave copies 64 rows of
+    // each tile, so one lane per row touches all of them: lane l takes row 8*(wave + 4*(l/8)) + l%8.
+    // Rows come from HBM (gathered x rows) or the memory-side cache (w), whose latency exceeds one step;
+    // touching them kPrefetch steps ahead lets the tile copies hit in L2.
+    uint32_t pf_w, pf_x;
+    {
+        const int r = 8 * (wave + 4 * (lane >> 3)) + (lane & 7);
+        int n = n0 + r;
+        if (n > a.c_out - 1) n = a.c_out - 1;
+        pf_w = (uint32_t)n * (uint32_t)a.c_in * 2u;
+        int m = m0 + r;
+        if (m > a.k_sel - 1) m = a.k_sel - 1;
+        const int64_t row = a.x_indexed ? (int64_t)a.idx_sel[m] : (int64_t)m;
+        pf_x = (uint32_t)(row * a.ldx * 2);
+    }
+    asm volatile("" ::"v"(pf_x), "v"(pf_w));
+    uint32_t sink_w = 0, sink_x = 0;
+    constexpr int kPrefetch = 3;
+    auto dma_w = [&](int t, int kstep, uint32_t stage) __attribute__((always_inline)) {
+        dma16(wg + (int64_t)kstep * kRowBytes, woff[t], lds0 + stage + (wave + 4 * t) * 1024);
+    };
+    auto dma_x = [&](int t, int kstep, uint32_t stage) __attribute__((always_inline)) {
+        dma16(xg + (int64_t)kstep * kRowBytes, xoff[t], lds0 + stage + kTileBytes + (wave + 4 * t) * 1024);
+    };
+
+    // ---- fragment addresses: row 32*block + qc of this wave's half, logical chunk 2*s + hf of k-step s
+    uint32_t wa[4], xa[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const uint32_t sw = (uint32_t)(((2 * s + hf) ^ ((qc >> 1) & 7)) << 4);
+        wa[s] = lds0 + (wn * 128 + qc) * kRowBytes + sw;
+        xa[s] = lds0 + kTileBytes + (wm * 128 + qc) * kRowBytes + sw;
+    }
+
+    floatx16 acc[4][4];                  // [feature block][token block]
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+    const int nk = a.c_in / kBk;
+    // prologue: first stage
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        dma_w(t, 0, 0);
+        dma_x(t, 0, 0);
+    }
+    for (int p = 1; p < kPrefetch; ++p) {
+        const int kp = p < nk ? p : nk - 1;
+        touch_line(wg + (int64_t)kp * kRowBytes, pf_w, sink_w);
+        touch_line(xg + (int64_t)kp * kRowBytes, pf_x, sink_x);
+    }
+    wait_dma();
+    __builtin_amdgcn_s_barrier();
+
+    uint32_t next_stage = kStageBytes;   // where the copies of step kk+1 go
+    for (int kk = 0; kk < nk; ++kk) {
+        // the last step has nothing to prefetch: it copies its own tiles again into the idle stage
+        // rather than branch around every copy
+        const int kn = kk + 1 < nk ? kk + 1 : kk;
+        const int kp = kk + kPrefetch < nk ? kk + kPrefetch : nk - 1;
+        bf16x8 wf[2][4], xf[2][4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            wf[0][i] = lds_read_b128(wa[0] + i * 32 * kRowBytes);
+            xf[0][i] = lds_read_b128(xa[0] + i * 32 * kRowBytes);
+        }
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int cur = s & 1, nxt = cur ^ 1;
+            if (s < 3) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    wf[nxt][i] = lds_read_b128(wa[s + 1] + i * 32 * kRowBytes);
+                    xf[nxt][i] = lds_read_b128(xa[s + 1] + i * 32 * kRowBytes);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                // the next step's copies go out during the first half of this one, two per four MFMAs, so that
+                // they have landed when the step ends
+                if (s < 2) {
+                    dma_w(4 * s + i, kn, next_stage);
+                    dma_x(4 * s + i, kn, next_stage);
+                }
+                if (s == 2 && i == 0) {          // after the copies, so that waiting for those leaves these pending
+                    touch_line(wg + (int64_t)kp * kRowBytes, pf_w, sink_w);
+                    touch_line(xg + (int64_t)kp * kRowBytes, pf_x, sink_x);
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[cur][i], xf[cur][j], acc[i][j], 0, 0, 0);
+            }
+        }
+        // the next step's tiles are complete and this step's are no longer read: swap stages
+        wait_dma_keep2();
+        __builtin_amdgcn_s_barrier();
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            wa[s] ^= kStageBytes;
+            xa[s] ^= kStageBytes;
+        }
+        next_stage ^= kStageBytes;
+    }
+
+    wait_dma();
+    asm volatile("" ::"v"(sink_w), "v"(sink_x));
+    // ---- epilogue: bias, activation, bf16; then through LDS so that global stores cover whole rows.
+    // Register group g of block (i, j): features 128*wn + 32*i + 8*g + 4*hf + 0..3, token
+    // 128*wm + 32*j + qc of the tile.  An accumulator lane owns one token, so stores straight from the
+    // registers would put 16 bytes on each of 32 rows per instruction; partial-line writes of that kind
+    // cost several times the main loop's share of HBM time.  Instead each wave transposes its 128 x 128
+    // block in two halves of 64 tokens through its own 17 KiB of LDS (rows of 128 features, pitch 272
+    // bytes) and writes 4 rows x 256 contiguous bytes per instruction.  The tile buffers are free: every
+    // wave has passed the barrier that ends the last step.  The region is private to the wave, so no
+    // workgroup barrier is needed, only the wave's own LDS counter.
+    constexpr int kPitch = 272;
+    // this lane's 64 bias values (16 groups of 4 features), fetched in one batch: a load inside the
+    // loops below would be waited for 64 times over
+    uint2v bias2[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            int n = n0 + wn * 128 + 32 * i + 8 * g + 4 * hf;
+            if (n > a.c_out - 4) n = a.c_out - 4;            // past the end: any valid address, the result is not stored
+            bias2[i][g] = uint2v{0u, 0u};
+            if (a.bias) bias2[i][g] = *reinterpret_cast<const uint2v *>(a.bias + n);
+        }
+    const uint32_t ebase = lds0 + wave * (64 * kPitch);
+    const int o_row = lane >> 4, o_chunk = lane & 15;      // read-back: 4 rows per instruction, 16 lanes x 16 B each
+#pragma unroll
+    for (int jh = 0; jh < 2; ++jh) {
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+            const int j = 2 * jh + jj;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int nl = 32 * i + 8 * g + 4 * hf;      // feature inside the wave's 128
+                    float v[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * g + e];
+                    const uint2v b2 = bias2[i][g];
+                    v[0] += __uint_as_float(b2[0] << 16);
+                    v[1] += __uint_as_float(b2[0] & 0xffff0000u);
+                    v[2] += __uint_as_float(b2[1] << 16);
+                    v[3] += __uint_as_float(b2[1] & 0xffff0000u);
+                    if (a.act == ASTRAEA_ACT_GELU_TANH) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] = gelu_tanh(v[e]);
+                    }
+                    uint2v o2;
+                    o2[0] = pack_bf16(v[0], v[1]);
+                    o2[1] = pack_bf16(v[2], v[3]);
+                    *reinterpret_cast<uint2v __attribute__((address_space(3))) *>(
+                        (uintptr_t)(ebase + (32 * jj + qc) * kPitch + nl * 2)) = o2;
+                }
+        }
+        __builtin_amdgcn_s_waitcnt(0xc07f);                      // lgkmcnt(0): this wave's LDS writes are done
+        // destination rows of this half first (16 per lane), then the stores: an index load between
+        // two stores would be waited for each time
+        int64_t orow[16];
+#pragma unroll
+        for (int it = 0; it < 16; ++it) {
+            int m = m0 + wm * 128 + 64 * jh + 4 * it + o_row;
+            if (m > a.k_sel - 1) m = a.k_sel - 1;
+            orow[it] = a.y_indexed ? (int64_t)a.idx_sel[m] : (int64_t)m;
+        }
+#pragma unroll
+        for (int it = 0; it < 16; ++it) {
+            const int tl = 4 * it + o_row;                       // token inside this half
+            const int m = m0 + wm * 128 + 64 * jh + tl;
+            const int n = n0 + wn * 128 + 8 * o_chunk;           // c_out is a multiple of 8: a chunk is all in or all out
+            const uint4v val = *reinterpret_cast<const uint4v __attribute__((address_space(3))) *>(
+                (uintptr_t)(ebase + tl * kPitch + o_chunk * 16));
+            if (m < a.k_sel && n < a.c_out) *reinterpret_cast<uint4v *>(a.y + orow[it] * a.ldy + n) = val;
+        }
+        __builtin_amdgcn_s_waitcnt(0xc07f);                      // reads done before the second half overwrites
+    }
+}
+
+}  // namespace
+
+int launch_linear_bf16(const void *x, const void *w, const void *bias, void *y, const int32_t *idx_sel, int64_t k_sel,
+                       int32_t c_in, int32_t c_out, int64_t ldx, int64_t ldy, int x_indexed, int y_indexed, int act,
+                       hipStream_t stream)
+{
+    if (k_sel == 0) return ASTRAEA_OK;
+    LinearArgs a;
+    a.x = (const __bf16 *)x;
+    a.w = (const __bf16 *)w;
+    a.bias = (const __bf16 *)bias;
+    a.y = (__bf16 *)y;
+    a.idx_sel = idx_sel;
+    a.ldx = ldx;
+    a.ldy = ldy;
+    a.k_sel = (int32_t)k_sel;
+    a.c_in = c_in;
+    a.c_out = c_out;
+    a.x_indexed = x_indexed;
+    a.y_indexed = y_indexed;
+    a.act = act;
+    a.m_tiles = (int32_t)((k_sel + kBm - 1) / kBm);
+    a.n_tiles = (c_out + kBn - 1) / kBn;
+    a.sb_n = (a.n_tiles + kSbN - 1) / kSbN;
+    const int64_t sb_m = (a.m_tiles + kSbM - 1) / kSbM;
+    const int64_t sbs = sb_m * a.sb_n;                                  // super-blocks, dealt round-robin to the XCDs
+    const int64_t rounds = (sbs + kNumXcd - 1) / kNumXcd;
+    const int64_t grid = rounds * kNumXcd * (kSbM * kSbN);
+    if (grid > 2147483647LL) return fail(ASTRAEA_ERR_INVALID, "astraea_sparse_linear: grid too large");
+    hipLaunchKernelGGL(linear_bf16_kernel, dim3((unsigned)grid), dim3(256), 0, stream, a);
+    return check_launch("astraea_sparse_linear(bf16)");
+}
+
+}  // namespace astraea
