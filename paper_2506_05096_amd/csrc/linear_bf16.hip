@@ -11,12 +11,15 @@
 //    v_mfma_f32_32x32x16_bf16 want (a lane holds 8 consecutive k of one row / column).  w feeds the A
 //    operand and x the B operand, so that an accumulator lane owns one token and 4 consecutive output
 //    features per register group: the epilogue packs them to 8-byte stores along the output row.
-//  * workgroup = 4 waves, one per SIMD, output tile 256 features x 256 tokens, each wave 128 x 128
-//    (4 x 4 MFMA blocks, 256 accumulator registers): one LDS fragment read per two MFMAs.
+//  * workgroup = 8 waves, two per SIMD, output tile 256 features x 256 tokens, each wave 128 features
+//    x 64 tokens (4 x 2 MFMA blocks, 128 accumulator registers, 3 LDS fragment reads per 4 MFMAs).
+//    One wave per SIMD with 128 x 128 (kWaves = 4) reads less from LDS but leaves the matrix pipe idle
+//    at every barrier; measured 2-4 % slower.
 //  * the contraction advances in steps of 64; the two 32 KiB tiles of a step go from global memory
 //    straight into LDS (global_load_lds_dwordx4, per-lane addresses, so the row gather costs nothing),
 //    double buffered, 16-byte chunks XOR-swizzled inside each 128-byte row against bank conflicts.
-//    The copy instructions of the next step are spread between the MFMAs of the current one.
+//    The copy instructions of the next step go out between the first MFMAs of the current one, and
+//    a 4-byte load per row touches the lines of three steps ahead so that the copies hit in L2.
 //  * workgroup ids are mapped so that the 32 workgroups resident on one XCD form an 8 x 4 block of
 //    tiles: they stream 8 row tiles and 4 weight tiles through that XCD's L2 instead of 32 + 32.
 #include "common.h"
@@ -37,6 +40,9 @@ constexpr int kBk = 64;                  // contraction step
 constexpr int kRowBytes = kBk * 2;       // 128 B of a row per step
 constexpr int kTileBytes = 256 * kRowBytes;          // 32 KiB
 constexpr int kStageBytes = 2 * kTileBytes;          // w tile, then x tile
+constexpr int kWaves = 8;                // 8: two per SIMD, 128 features x 64 tokens each; 4: one per SIMD, 128 x 128 each
+constexpr int kTb = 16 / kWaves;         // 32-token MFMA blocks per wave
+constexpr int kCopies = 32 / kWaves;     // 1 KiB copy instructions per wave and tile
 constexpr int kNumXcd = 8;
 constexpr int kSbM = 8, kSbN = 4;        // tiles of one XCD round: 8 token tiles x 4 feature tiles
 
@@ -88,11 +94,13 @@ struct LinearArgs {
     int32_t m_tiles, n_tiles, sb_n;   // tile counts and 4-wide super-block count along the features
 };
 
-__global__ __launch_bounds__(256, 1) void linear_bf16_kernel(LinearArgs a)
+__global__ __launch_bounds__(kWaves *kWave, 1) void linear_bf16_kernel(LinearArgs a)
 {
     // [stage][w tile | x tile]; the only LDS object of the kernel, so it starts at LDS address 0, which
     // the stage flips (XOR) rely on.
-    __shared__ __attribute__((aligned(1024))) char lds[2 * kStageBytes];
+    constexpr int kPitch = 272;          // epilogue staging: 128 features of a token, padded
+    constexpr int kEpiBytes = kWaves * 64 * kPitch;   // every wave stages 64 tokens at a time
+    __shared__ __attribute__((aligned(1024))) char lds[2 * kStageBytes > kEpiBytes ? 2 * kStageBytes : kEpiBytes];
 
     // ---- which tile: workgroup ids reach the XCDs round-robin; each XCD takes every 8th super-block
     // of 8 x 4 tiles and runs its 32 tiles at the same time.
@@ -106,7 +114,7 @@ __global__ __launch_bounds__(256, 1) void linear_bf16_kernel(LinearArgs a)
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int qc = lane & 31, hf = lane >> 5;
-    const int wn = wave & 1, wm = wave >> 1;          // this wave's 128-feature and 128-token halves
+    const int wn = wave & 1, wm = wave >> 1;          // this wave's 128 features and 32*kTb tokens of the tile
     const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
 
     // ---- tile copies.  One instruction fills 1 KiB = 8 rows of a tile; wave w issues instructions
@@ -115,10 +123,10 @@ __global__ __launch_bounds__(256, 1) void linear_bf16_kernel(LinearArgs a)
     // instructions, so a lane's byte offset inside its rows is fixed.
     const int d_row = lane >> 3;
     const int lchunk = (lane & 7) ^ ((4 * (wave & 1) + (lane >> 4)) & 7);
-    uint32_t woff[8], xoff[8];           // byte offsets of this lane's rows from w and x
+    uint32_t woff[kCopies], xoff[kCopies];   // byte offsets of this lane's rows from w and x
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {
-        const int r = 8 * (wave + 4 * t) + d_row;
+    for (int t = 0; t < kCopies; ++t) {
+        const int r = 8 * (wave + kWaves * t) + d_row;
         int n = n0 + r;                  // rows past the end re-read the last one; they are never stored
         if (n > a.c_out - 1) n = a.c_out - 1;
         woff[t] = (uint32_t)n * (uint32_t)a.c_in * 2u + (uint32_t)lchunk * 16u;
@@ -130,17 +138,17 @@ __global__ __launch_bounds__(256, 1) void linear_bf16_kernel(LinearArgs a)
     // all index loads must have landed before the loop: a load still pending at the loop header would
     // make the compiler wait on the vector-memory counter inside it
 #pragma unroll
-    for (int t = 0; t < 8; ++t) asm volatile("" ::"v"(xoff[t]), "v"(woff[t]));
+    for (int t = 0; t < kCopies; ++t) asm volatile("" ::"v"(xoff[t]), "v"(woff[t]));
 
     const char *wg = reinterpret_cast<const char *>(a.w);
     const char *xg = reinterpret_cast<const char *>(a.x);
     // L2 warm-up: a step's 128 bytes of one row are one cache line, and this wave copies 64 rows of
-    // each tile, so one lane per row touches all of them: lane l takes row 8*(wave + 4*(l/8)) + l%8.
+    // each tile, so one lane per row touches all of them (lane l: the l/8-th copy's row l%8).
     // Rows come from HBM (gathered x rows) or the memory-side cache (w), whose latency exceeds one step;
     // touching them kPrefetch steps ahead lets the tile copies hit in L2.
     uint32_t pf_w, pf_x;
     {
-        const int r = 8 * (wave + 4 * (lane >> 3)) + (lane & 7);
+        const int r = 8 * (wave + kWaves * ((lane >> 3) % kCopies)) + (lane & 7);
         int n = n0 + r;
         if (n > a.c_out - 1) n = a.c_out - 1;
         pf_w = (uint32_t)n * (uint32_t)a.c_in * 2u;
@@ -153,10 +161,10 @@ __global__ __launch_bounds__(256, 1) void linear_bf16_kernel(LinearArgs a)
     uint32_t sink_w = 0, sink_x = 0;
     constexpr int kPrefetch = 3;
     auto dma_w = [&](int t, int kstep, uint32_t stage) __attribute__((always_inline)) {
-        dma16(wg + (int64_t)kstep * kRowBytes, woff[t], lds0 + stage + (wave + 4 * t) * 1024);
+        dma16(wg + (int64_t)kstep * kRowBytes, woff[t], lds0 + stage + (wave + kWaves * t) * 1024);
     };
     auto dma_x = [&](int t, int kstep, uint32_t stage) __attribute__((always_inline)) {
-        dma16(xg + (int64_t)kstep * kRowBytes, xoff[t], lds0 + stage + kTileBytes + (wave + 4 * t) * 1024);
+        dma16(xg + (int64_t)kstep * kRowBytes, xoff[t], lds0 + stage + kTileBytes + (wave + kWaves * t) * 1024);
     };
 
     // ---- fragment addresses: row 32*block + qc of this wave's half, logical chunk 2*s + hf of k-step s
@@ -165,21 +173,21 @@ __global__ __launch_bounds__(256, 1) void linear_bf16_kernel(LinearArgs a)
     for (int s = 0; s < 4; ++s) {
         const uint32_t sw = (uint32_t)(((2 * s + hf) ^ ((qc >> 1) & 7)) << 4);
         wa[s] = lds0 + (wn * 128 + qc) * kRowBytes + sw;
-        xa[s] = lds0 + kTileBytes + (wm * 128 + qc) * kRowBytes + sw;
+        xa[s] = lds0 + kTileBytes + (wm * 32 * kTb + qc) * kRowBytes + sw;
     }
 
-    floatx16 acc[4][4];                  // [feature block][token block]
+    floatx16 acc[4][kTb];                // [feature block][token block]
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < kTb; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
     const int nk = a.c_in / kBk;
     // prologue: first stage
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {
+    for (int t = 0; t < kCopies; ++t) {
         dma_w(t, 0, 0);
         dma_x(t, 0, 0);
     }
@@ -197,27 +205,25 @@ __global__ __launch_bounds__(256, 1) void linear_bf16_kernel(LinearArgs a)
         // rather than branch around every copy
         const int kn = kk + 1 < nk ? kk + 1 : kk;
         const int kp = kk + kPrefetch < nk ? kk + kPrefetch : nk - 1;
-        bf16x8 wf[2][4], xf[2][4];
+        bf16x8 wf[2][4], xf[2][kTb];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            wf[0][i] = lds_read_b128(wa[0] + i * 32 * kRowBytes);
-            xf[0][i] = lds_read_b128(xa[0] + i * 32 * kRowBytes);
-        }
+        for (int i = 0; i < 4; ++i) wf[0][i] = lds_read_b128(wa[0] + i * 32 * kRowBytes);
+#pragma unroll
+        for (int j = 0; j < kTb; ++j) xf[0][j] = lds_read_b128(xa[0] + j * 32 * kRowBytes);
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             const int cur = s & 1, nxt = cur ^ 1;
             if (s < 3) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    wf[nxt][i] = lds_read_b128(wa[s + 1] + i * 32 * kRowBytes);
-                    xf[nxt][i] = lds_read_b128(xa[s + 1] + i * 32 * kRowBytes);
-                }
+                for (int i = 0; i < 4; ++i) wf[nxt][i] = lds_read_b128(wa[s + 1] + i * 32 * kRowBytes);
+#pragma unroll
+                for (int j = 0; j < kTb; ++j) xf[nxt][j] = lds_read_b128(xa[s + 1] + j * 32 * kRowBytes);
             }
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 // the next step's copies go out during the first half of this one, two per four MFMAs, so that
                 // they have landed when the step ends
-                if (s < 2) {
+                if (4 * s + i < kCopies) {
                     dma_w(4 * s + i, kn, next_stage);
                     dma_x(4 * s + i, kn, next_stage);
                 }
@@ -226,7 +232,7 @@ __global__ __launch_bounds__(256, 1) void linear_bf16_kernel(LinearArgs a)
                     touch_line(xg + (int64_t)kp * kRowBytes, pf_x, sink_x);
                 }
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
+                for (int j = 0; j < kTb; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[cur][i], xf[cur][j], acc[i][j], 0, 0, 0);
             }
         }
@@ -245,14 +251,13 @@ __global__ __launch_bounds__(256, 1) void linear_bf16_kernel(LinearArgs a)
     asm volatile("" ::"v"(sink_w), "v"(sink_x));
     // ---- epilogue: bias, activation, bf16; then through LDS so that global stores cover whole rows.
     // Register group g of block (i, j): features 128*wn + 32*i + 8*g + 4*hf + 0..3, token
-    // 128*wm + 32*j + qc of the tile.  An accumulator lane owns one token, so stores straight from the
+    // 32*kTb*wm + 32*j + qc of the tile.  An accumulator lane owns one token, so stores straight from the
     // registers would put 16 bytes on each of 32 rows per instruction; partial-line writes of that kind
-    // cost several times the main loop's share of HBM time.  Instead each wave transposes its 128 x 128
-    // block in two halves of 64 tokens through its own 17 KiB of LDS (rows of 128 features, pitch 272
+    // cost several times the main loop's share of HBM time.  Instead each wave transposes its block,
+    // 64 tokens at a time, through its own 17 KiB of LDS (rows of 128 features, pitch 272
     // bytes) and writes 4 rows x 256 contiguous bytes per instruction.  The tile buffers are free: every
     // wave has passed the barrier that ends the last step.  The region is private to the wave, so no
     // workgroup barrier is needed, only the wave's own LDS counter.
-    constexpr int kPitch = 272;
     // this lane's 64 bias values (16 groups of 4 features), fetched in one batch: a load inside the
     // loops below would be waited for 64 times over
     uint2v bias2[4][4];
@@ -268,7 +273,7 @@ __global__ __launch_bounds__(256, 1) void linear_bf16_kernel(LinearArgs a)
     const uint32_t ebase = lds0 + wave * (64 * kPitch);
     const int o_row = lane >> 4, o_chunk = lane & 15;      // read-back: 4 rows per instruction, 16 lanes x 16 B each
 #pragma unroll
-    for (int jh = 0; jh < 2; ++jh) {
+    for (int jh = 0; jh < kTb / 2; ++jh) {
 #pragma unroll
         for (int jj = 0; jj < 2; ++jj) {
             const int j = 2 * jh + jj;
@@ -302,14 +307,14 @@ __global__ __launch_bounds__(256, 1) void linear_bf16_kernel(LinearArgs a)
         int64_t orow[16];
 #pragma unroll
         for (int it = 0; it < 16; ++it) {
-            int m = m0 + wm * 128 + 64 * jh + 4 * it + o_row;
+            int m = m0 + wm * 32 * kTb + 64 * jh + 4 * it + o_row;
             if (m > a.k_sel - 1) m = a.k_sel - 1;
             orow[it] = a.y_indexed ? (int64_t)a.idx_sel[m] : (int64_t)m;
         }
 #pragma unroll
         for (int it = 0; it < 16; ++it) {
             const int tl = 4 * it + o_row;                       // token inside this half
-            const int m = m0 + wm * 128 + 64 * jh + tl;
+            const int m = m0 + wm * 32 * kTb + 64 * jh + tl;
             const int n = n0 + wn * 128 + 8 * o_chunk;           // c_out is a multiple of 8: a chunk is all in or all out
             const uint4v val = *reinterpret_cast<const uint4v __attribute__((address_space(3))) *>(
                 (uintptr_t)(ebase + tl * kPitch + o_chunk * 16));
@@ -348,7 +353,7 @@ int launch_linear_bf16(const void *x, const void *w, const void *bias, void *y, 
     const int64_t rounds = (sbs + kNumXcd - 1) / kNumXcd;
     const int64_t grid = rounds * kNumXcd * (kSbM * kSbN);
     if (grid > 2147483647LL) return fail(ASTRAEA_ERR_INVALID, "astraea_sparse_linear: grid too large");
-    hipLaunchKernelGGL(linear_bf16_kernel, dim3((unsigned)grid), dim3(256), 0, stream, a);
+    hipLaunchKernelGGL(linear_bf16_kernel, dim3((unsigned)grid), dim3(kWaves * kWave), 0, stream, a);
     return check_launch("astraea_sparse_linear(bf16)");
 }
 
