@@ -141,6 +141,51 @@ def library_context(torch, w, k):
     return out
 
 
+def token_sparse_block(torch, ab, w, t, k, reps=5):
+    """The per-token layers of a block on the k selected rows (Q/K/V and output projections, two MLP layers, each
+    one astraea_sparse_linear call with synthetic bf16 weights) and the whole block step with them.  Reported
+    beside the headline; the flops are 2*k*c_in*c_out per layer (the projection and MLP terms of the paper's FLOPs
+    appendix with N -> k)."""
+    from paper_2506_05096_amd.layer import TokenSparseBlock
+    E, hid, dev = w.H * w.D, 4 * w.H * w.D, t["q"].device
+    g = torch.Generator(device=dev).manual_seed(4242)
+    mk = lambda o, i: (torch.randn(o, i, device=dev, generator=g) * i ** -0.5).bfloat16()
+    weights = {"wq": mk(E, E), "wk": mk(E, E), "wv": mk(E, E), "wo": mk(E, E), "w1": mk(hid, E), "w2": mk(E, hid),
+               "b1": torch.zeros(hid, dtype=torch.bfloat16, device=dev), "b2": torch.zeros(E, dtype=torch.bfloat16, device=dev)}
+    blk = TokenSparseBlock(w.N, w.H, w.D, weights, device=dev)
+    tt = {"x_in": t["x_cur"], "x_prev": t["x_prev"], "k_cache": t["k_cache"], "v_cache": t["v_cache"],
+          "out_cache": t["out_cache"]}
+    if tt["x_in"].shape[1] != E:
+        return {"skipped": "feature width of this workload is not H*D"}
+    blk.run(tt, k)
+    torch.cuda.synchronize()
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    parts = {"qkv_proj": lambda: blk.step_qkv(tt, k), "attn": lambda: blk.step_attn(tt, k),
+             "out_proj_mlp": lambda: blk.step_proj_mlp(tt, k)}
+    ms = {}
+    for nm, fn in parts.items():
+        a, b = ev(), ev()
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        ms[nm] = a.elapsed_time(b) / reps
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        blk.run(tt, k)
+    torch.cuda.synchronize()
+    step_ms = (time.perf_counter() - t0) * 1e3 / reps
+    fl_qkv, fl_rest = 2.0 * k * E * 3 * E, 2.0 * k * (E * E + 2 * E * hid)
+    lin_ms = ms["qkv_proj"] + ms["out_proj_mlp"]
+    return {"ms_per_step": step_ms, "ms": ms,
+            "linear_TFLOPs": (fl_qkv + fl_rest) / lin_ms / 1e9,
+            "linear_frac_of_mfma_peak": (fl_qkv + fl_rest) / lin_ms / 1e9 / PEAK_TFLOPS["bf16"],
+            "linear_flops": fl_qkv + fl_rest,
+            "what": "score + top-k + 3 projections of the selected rows (K/V written into the caches) + attention + "
+                    "output projection + 2 MLP layers (the last writes the cached block output); hidden width 4*H*D"}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -270,6 +315,8 @@ def main() -> int:
         "hbm_GBps": gbs,
         "hbm_frac_of_8TBps": {k_: v_ / PEAK_HBM_GBS for k_, v_ in gbs.items()},
     }
+    if w.dtype == "bf16" and w.D == 128:
+        out["token_sparse_block"] = token_sparse_block(torch, ab, w, t, k)
     out["measured_peaks"] = measured_peaks(torch, ab)
     if args.context:
         out["library_context_same_gpu"] = library_context(torch, w, k)

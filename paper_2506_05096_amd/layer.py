@@ -113,3 +113,59 @@ class StatefulLayer(LayerStep):
             self.step_attn(t, k, lse=self.lse_sel[:max(k, 1)])
             self.step_state(t, k)
             self.step_scatter(t, k)
+
+
+class TokenSparseBlock(LayerStep):
+    """A whole token-wise block on the selected tokens (paper Sec. 3.2: "each token is processed
+    independently" in every layer but the attention, so all of them are computed for the selected tokens only
+    and the block's cached output serves the rest; Algorithm 1 steps 4-7; FLOPs appendix: Q/K/V projection,
+    attention, output projection, two MLP layers).  Layer norms, modulation and residual sums of a real DiT
+    block are not part of the paper's algorithm and are left out.
+
+    Weights are [c_out, c_in] bf16 tensors supplied by the caller (synthetic in the tests and the benchmark).
+    K and V of the selected tokens are written straight into the cached K/V by the projection (the cache
+    refresh fused into its producer), the MLP's second layer writes straight into the cached block output.
+    """
+
+    def __init__(self, N: int, H: int, D: int, weights: Dict[str, torch.Tensor], device="cuda", mlp_ratio: int = 4):
+        super().__init__(N, H, D, torch.bfloat16, device)
+        E = H * D
+        self.E, self.hidden = E, mlp_ratio * E
+        self.w = weights            # wq wk wv wo [E, E]; w1 [hidden, E]; w2 [E, hidden]; optional b* biases
+        bf = dict(dtype=torch.bfloat16, device=device)
+        self.q_sel = torch.empty((N, H, D), **bf)
+        self.h_sel = torch.empty((N, E), **bf)           # output projection result
+        self.m_sel = torch.empty((N, self.hidden), **bf)  # MLP hidden activations
+
+    def _b(self, name):
+        return self.w.get(name)
+
+    def step_qkv(self, t: Dict[str, torch.Tensor], k: int) -> None:
+        N, E, idx = self.N, self.E, self.idx_sel
+        x = t["x_in"]
+        ab.astraea_sparse_linear(x, self.w["wq"], self._b("bq"), idx, k, self.q_sel.view(N, E)[:max(k, 1)])
+        ab.astraea_sparse_linear(x, self.w["wk"], self._b("bk"), idx, k, t["k_cache"].view(N, E), y_is_compact=False)
+        ab.astraea_sparse_linear(x, self.w["wv"], self._b("bv"), idx, k, t["v_cache"].view(N, E), y_is_compact=False)
+
+    def step_attn(self, t: Dict[str, torch.Tensor], k: int, lse: Optional[torch.Tensor] = None) -> None:
+        ab.astraea_sparse_attn_fwd(self.q_sel[:max(k, 1)], t["k_cache"], t["v_cache"], self.idx_sel, k,
+                                   self.o_sel[:max(k, 1)], self.scale, q_is_compact=True, lse_sel=lse,
+                                   workspace=self.attn_ws)
+
+    def step_proj_mlp(self, t: Dict[str, torch.Tensor], k: int) -> None:
+        N, E, kk = self.N, self.E, max(k, 1)
+        ab.astraea_sparse_linear(self.o_sel.view(N, E)[:kk], self.w["wo"], self._b("bo"), None, k, self.h_sel[:kk],
+                                 x_is_compact=True)
+        ab.astraea_sparse_linear(self.h_sel[:kk], self.w["w1"], self._b("b1"), None, k, self.m_sel[:kk],
+                                 act=ab.ACT_GELU_TANH, x_is_compact=True)
+        ab.astraea_sparse_linear(self.m_sel[:kk], self.w["w2"], self._b("b2"), self.idx_sel, k, t["out_cache"],
+                                 x_is_compact=True, y_is_compact=False, N=N)
+
+    def run(self, t: Dict[str, torch.Tensor], k: int) -> None:
+        """score -> top-k -> Q/K/V projections of the selected rows (K/V into the caches) -> attention ->
+        output projection -> MLP, whose last layer updates the cached block output in place."""
+        ab.astraea_score(t["x_in"], t["x_prev"], self.score)
+        self.step_select(k)
+        self.step_qkv(t, k)
+        self.step_attn(t, k)
+        self.step_proj_mlp(t, k)

@@ -135,6 +135,27 @@ def test_sparse_attn_update_rejects_bad_arguments(L):
     assert call(k_sel=0, q=None, out=None, idx=None) == ab.OK   # budget 0 leaves the cache as it is
 
 
+def test_sparse_linear_rejects_bad_arguments(L):
+    f = L.astraea_sparse_linear
+
+    def call(dt=ab.BF16, N=100, cin=128, cout=64, xs=128, idx=FAKE, k_sel=10, xc=0, act=0, ys=64, yc=1, x=FAKE, w=FAKE,
+             b=None, y=FAKE):
+        return f(x, w, b, dt, N, cin, cout, xs, idx, k_sel, xc, act, y, ys, yc, None)
+
+    assert call(dt=ab.F32) == ab.ERR_UNSUPPORTED                # bf16 only
+    assert call(dt=9) == ab.ERR_UNSUPPORTED
+    assert call(act=2) == ab.ERR_UNSUPPORTED
+    assert call(cin=96, xs=96) == ab.ERR_UNSUPPORTED            # contraction advances in steps of 64
+    assert call(cout=60, ys=64) == ab.ERR_UNSUPPORTED
+    assert call(xs=64) == ab.ERR_INVALID and call(ys=32) == ab.ERR_INVALID and call(xs=132) == ab.ERR_INVALID
+    assert call(k_sel=101) == ab.ERR_INVALID and call(k_sel=-1) == ab.ERR_INVALID
+    assert call(idx=None) == ab.ERR_INVALID                     # rows must be gathered
+    assert call(idx=None, xc=1, yc=0) == ab.ERR_INVALID         # rows must be placed
+    assert call(x=None) == ab.ERR_INVALID and call(y=FAKE + 8) == ab.ERR_INVALID and call(b=FAKE + 4) == ab.ERR_INVALID
+    assert call(N=1 << 21, xs=1 << 11, cin=1 << 11) == ab.ERR_UNSUPPORTED    # x spans 8 GiB: beyond 32-bit offsets
+    assert call(k_sel=0, x=None, w=None, y=None, idx=None) == ab.OK
+
+
 def test_row_movers_reject_bad_arguments(L):
     sc, ga = L.astraea_scatter_update, L.astraea_gather_rows
     assert sc(FAKE, FAKE, 5, 10, 8, 8, 8, FAKE, 3, 0, None) == ab.ERR_UNSUPPORTED

@@ -1,0 +1,81 @@
+"""The whole token-wise block on the selected tokens (paper Sec. 3.2; Algorithm 1 steps 1-7 with the per-token
+layers of the FLOPs appendix) against the oracle, stage by stage: every stage of the oracle starts from the bf16
+values the GPU produced for the stage before it, so each comparison isolates one kernel."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from conftest import bf16_bits_to_f64, to_np
+from paper_2506_05096_amd import binding as ab
+from paper_2506_05096_amd.layer import TokenSparseBlock
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def _rel(a, b):
+    return float(np.linalg.norm((a - b).ravel()) / np.linalg.norm(b.ravel()))
+
+
+def test_block_matches_oracle_stage_by_stage():
+    n, H, D, budget = 1300, 2, 128, 35
+    E, hid = H * D, 4 * H * D
+    g = torch.Generator().manual_seed(13)
+    rnd = lambda *s, sc=1.0: (torch.randn(*s, generator=g) * sc).bfloat16()
+    w = {"wq": rnd(E, E, sc=E ** -0.5), "wk": rnd(E, E, sc=E ** -0.5), "wv": rnd(E, E, sc=E ** -0.5),
+         "wo": rnd(E, E, sc=E ** -0.5), "w1": rnd(hid, E, sc=E ** -0.5), "w2": rnd(E, hid, sc=hid ** -0.5),
+         "bq": rnd(E, sc=0.1), "b1": rnd(hid, sc=0.1), "b2": rnd(E, sc=0.1)}
+    t = {"x_prev": rnd(n, E), "k_cache": rnd(n, H, D), "v_cache": rnd(n, H, D), "out_cache": rnd(n, E)}
+    t["x_in"] = (t["x_prev"].float() + 0.1 * torch.randn(n, E, generator=g)).bfloat16()
+    host = {k_: to_np(v) for k_, v in t.items()}
+    hw = {k_: to_np(v) for k_, v in w.items()}
+    t = {k_: v.to(DEV) for k_, v in t.items()}
+    blk = TokenSparseBlock(n, H, D, {k_: v.to(DEV) for k_, v in w.items()}, device=DEV)
+    k = blk.budget_to_k(budget)
+    blk.run(t, k)
+    torch.cuda.synchronize()
+
+    # selection: bit-exact
+    so = oracle.score(host["x_in"], host["x_prev"], oracle.DELTA_L2)
+    e_idx, e_rem, _ = oracle.topk(so, k)
+    assert np.array_equal(blk.idx_sel[:k].cpu().numpy(), e_idx)
+    # projections of the selected rows
+    q_gpu = to_np(blk.q_sel.view(n, E)[:k])
+    assert _rel(bf16_bits_to_f64(q_gpu), oracle.sparse_linear(host["x_in"], hw["wq"], e_idx, bias=hw["bq"])) <= 1e-2
+    kc, vc = to_np(t["k_cache"]).reshape(n, E), to_np(t["v_cache"]).reshape(n, E)
+    for got, name, wn in ((kc, "k_cache", "wk"), (vc, "v_cache", "wv")):
+        ref = oracle.sparse_linear(host["x_in"], hw[wn], e_idx)
+        assert _rel(bf16_bits_to_f64(got[e_idx]), ref) <= 1e-2
+        assert np.array_equal(got[e_rem], host[name].reshape(n, E)[e_rem])          # cached rows of the others kept
+    # attention on the GPU's own Q and refreshed K/V
+    o64, _ = oracle.sparse_attn(q_gpu.reshape(k, H, D), kc.reshape(n, H, D), vc.reshape(n, H, D), None,
+                                1.0 / math.sqrt(D), q_is_compact=True)
+    o_gpu = to_np(blk.o_sel.view(n, E)[:k])
+    assert _rel(bf16_bits_to_f64(o_gpu), o64.reshape(k, E)) <= 1e-2
+    # output projection, MLP
+    h_gpu = to_np(blk.h_sel[:k])
+    assert _rel(bf16_bits_to_f64(h_gpu), oracle.sparse_linear(o_gpu, hw["wo"], None, x_is_compact=True)) <= 1e-2
+    m_gpu = to_np(blk.m_sel[:k])
+    ref = oracle.sparse_linear(h_gpu, hw["w1"], None, bias=hw["b1"], act=oracle.ACT_GELU_TANH, x_is_compact=True)
+    assert _rel(bf16_bits_to_f64(m_gpu), ref) <= 1e-2
+    out = to_np(t["out_cache"])
+    ref = oracle.sparse_linear(m_gpu, hw["w2"], None, bias=hw["b2"], x_is_compact=True)
+    assert _rel(bf16_bits_to_f64(out[e_idx]), ref) <= 1e-2
+    assert np.array_equal(out[e_rem], host["out_cache"][e_rem])                      # block output of the others reused
+
+
+def test_block_budget_zero_changes_nothing():
+    n, H, D = 300, 1, 128
+    E = H * D
+    g = torch.Generator().manual_seed(1)
+    rnd = lambda *s: torch.randn(*s, generator=g).bfloat16().to(DEV)
+    w = {"wq": rnd(E, E), "wk": rnd(E, E), "wv": rnd(E, E), "wo": rnd(E, E), "w1": rnd(4 * E, E), "w2": rnd(E, 4 * E)}
+    t = {"x_prev": rnd(n, E), "x_in": rnd(n, E), "k_cache": rnd(n, H, D), "v_cache": rnd(n, H, D), "out_cache": rnd(n, E)}
+    before = {k_: v.clone() for k_, v in t.items()}
+    TokenSparseBlock(n, H, D, w, device=DEV).run(t, 0)
+    torch.cuda.synchronize()
+    for k_ in t:
+        assert torch.equal(t[k_], before[k_]), k_
