@@ -315,6 +315,35 @@ def test_attn_bf16_split_items_match_oracle(n, h, k_sel):
     assert np.array_equal(o, o2)
 
 
+@pytest.mark.parametrize("dtype,d,n_ctx,k_sel", [(torch.bfloat16, 128, 77, 1000), (torch.bfloat16, 128, 256, 5000),
+                                                  (torch.float32, 64, 120, 700)])
+def test_cross_attention_of_selected_rows(dtype, d, n_ctx, k_sel):
+    """Cross-attention is a per-token layer too (each video token attends to the same short context), so it is
+    computed for the selected rows only: compact queries of the selected tokens, keys/values of another, shorter
+    sequence.  More queries than keys, a key count far below one key tile's multiple."""
+    h = 3
+    g = torch.Generator().manual_seed(n_ctx)
+    q = torch.randn(k_sel, h, d, generator=g).to(dtype)
+    k = torch.randn(n_ctx, h, d, generator=g).to(dtype)
+    v = torch.randn(n_ctx, h, d, generator=g).to(dtype)
+    scale = 1.0 / math.sqrt(d)
+    eo, else_ = oracle.sparse_attn(to_np(q), to_np(k), to_np(v), None, scale, q_is_compact=True)
+    o = torch.full((k_sel, h, d), float("nan"), dtype=dtype, device=DEV)
+    lse = torch.full((k_sel, h), float("nan"), device=DEV)
+    wsb = ab.workspace_bytes(ab.OP_SPARSE_ATTN, n_ctx, k_sel, h, d)
+    ws = torch.empty(max(wsb, 1), dtype=torch.uint8, device=DEV) if wsb else None
+    ab.astraea_sparse_attn_fwd(q.to(DEV), k.to(DEV), v.to(DEV), None, k_sel, o, scale, q_is_compact=True, lse_sel=lse,
+                               workspace=ws)
+    _sync()
+    got = as_f64(to_np(o))
+    if dtype == torch.float32:
+        assert np.max(np.abs(got - eo)) <= 1e-4
+    else:
+        assert _rel_l2(got, eo) <= 1e-2
+    # the bf16 kernel sums the bf16-rounded probabilities (the values its second product uses): few keys, little averaging
+    assert np.max(np.abs(lse.cpu().numpy() - else_)) <= (1e-4 if dtype == torch.float32 else 1e-3)
+
+
 # ------------------------------------------- attention fused with the cache update --
 
 @pytest.mark.parametrize("dtype,n,h,d,k_sel,pad", [
