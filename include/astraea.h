@@ -185,6 +185,49 @@ int astraea_sparse_linear(const void *x, const void *w, const void *bias, astrae
                           void *stream);
 
 /*
+ * Token-budget search (Sec. 3.3 "Algorithm"; supplementary algorithm "Evolutionary Search for Token
+ * Scheduling").  Host-only: no GPU work, every pointer is host memory.  A schedule is T int32 levels in
+ * tenths, theta_i in 0..10 for 0 %..100 % of the tokens at timestep i; budget_tenths is the target sum and
+ * [ceil(0.9 B), floor(1.1 B)] the accepted range.  Random draws come from SplitMix64 seeded by the caller
+ * (below(n) = floor(next*n / 2^64), unit() = (next >> 11) * 2^-53), so a seed fixes the result.
+ *
+ * astraea_budget_search: `population` random schedules are repaired into the range; per generation g = 1..G
+ * `children` new ones are made, each from a random pair of distinct parents of the current population by
+ * crossover (uniform or block, chosen with equal probability), mutation with probability
+ * P(g) = p_mutation_start - (g/G)(p_mutation_start - p_mutation_final) per timestep, and repair, dropped
+ * if already present (at most 64*children draws per generation); all are evaluated with `fitness` (lower is
+ * better; called once per new candidate) and the best `population` survive, ties keeping the earlier one.
+ *   best_theta [T] out; best_fitness out or NULL; population_out [population*T] and fitness_out
+ *   [population] (best first) out or NULL; population_size_out (<= population) out or NULL.
+ * The operator entry points apply one step to caller-held schedules and advance *rng_state (the SplitMix64
+ * state): crossover kind ASTRAEA_CROSSOVER_UNIFORM takes each level from either parent with equal
+ * probability; _BLOCK takes a contiguous range [min(a,b), max(a,b)), a and b drawn from 0..T, from parent0
+ * and the rest from parent1; mutate redraws a level from 0..10 with probability p_mutation; repair lowers
+ * (raises) random levels one tenth at a time, drawn among those that can still move, until the sum is in
+ * range, and draws nothing if it already is.  Errors: ASTRAEA_ERR_INVALID for NULL, sizes, probabilities or
+ * levels out of range.
+ */
+typedef double (*astraea_fitness_fn)(const int32_t *theta_tenths, int32_t T, void *user);
+typedef struct {
+    int32_t T;                 /* timesteps */
+    int32_t population;        /* K: candidates kept per generation (the paper uses 50) */
+    int32_t children;          /* P: new candidates per generation (30) */
+    int32_t generations;       /* G (30) */
+    int64_t budget_tenths;     /* target sum of the levels */
+    double p_mutation_start;   /* P_0 */
+    double p_mutation_final;   /* P_final */
+    uint64_t seed;
+} astraea_search_config;
+enum { ASTRAEA_CROSSOVER_UNIFORM = 0, ASTRAEA_CROSSOVER_BLOCK = 1 };
+int astraea_budget_search(const astraea_search_config *cfg, astraea_fitness_fn fitness, void *user,
+                          int32_t *best_theta, double *best_fitness, int32_t *population_out, double *fitness_out,
+                          int32_t *population_size_out);
+int astraea_search_crossover(const int32_t *parent0, const int32_t *parent1, int32_t T, int kind, uint64_t *rng_state,
+                             int32_t *child);
+int astraea_search_mutate(int32_t *theta, int32_t T, double p_mutation, uint64_t *rng_state);
+int astraea_search_repair(int32_t *theta, int32_t T, int64_t budget_tenths, uint64_t *rng_state);
+
+/*
  * astraea_lse_weight_update - carries the softmax by-product S_LSE of the selection metric to the
  * next timestep (Sec. 3.2 "Selection Metric": S_sig = S_LSE,t-1 * Delta_token,t, where S_LSE is the
  * row sum of exponentials the softmax computes anyway).  For every selected token

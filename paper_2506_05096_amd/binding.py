@@ -22,13 +22,25 @@ DELTA_L2, DELTA_MEAN_ABS, DELTA_MEAN_SQ = 0, 1, 2
 OK, ERR_INVALID, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
 OP_SELECT_TOPK, OP_SPARSE_ATTN = 1, 2
 ACT_NONE, ACT_GELU_TANH = 0, 1
+CROSSOVER_UNIFORM, CROSSOVER_BLOCK = 0, 1
 
 EXPORTS = (
     "astraea_score", "astraea_select_topk", "astraea_sparse_attn_fwd", "astraea_sparse_attn_update_fwd",
     "astraea_scatter_update", "astraea_gather_rows", "astraea_sparse_linear", "astraea_workspace_bytes", "astraea_budget_to_k", "astraea_attn_flops",
     "astraea_probe_mfma_bf16", "astraea_probe_copy", "astraea_lse_weight_update",
+    "astraea_budget_search", "astraea_search_crossover", "astraea_search_mutate", "astraea_search_repair",
     "astraea_status_string", "astraea_last_error",
 )
+
+
+class SearchConfig(C.Structure):
+    """astraea_search_config"""
+    _fields_ = [("T", C.c_int32), ("population", C.c_int32), ("children", C.c_int32), ("generations", C.c_int32),
+                ("budget_tenths", C.c_int64), ("p_mutation_start", C.c_double), ("p_mutation_final", C.c_double),
+                ("seed", C.c_uint64)]
+
+
+FITNESS_FN = C.CFUNCTYPE(C.c_double, C.POINTER(C.c_int32), C.c_int32, C.c_void_p)
 
 
 class AstraeaError(RuntimeError):
@@ -75,6 +87,14 @@ def lib() -> C.CDLL:
         L.astraea_probe_copy.argtypes = [vp, vp, i64, vp]
         L.astraea_probe_mfma_bf16.restype = C.c_int
         L.astraea_probe_copy.restype = C.c_int
+        L.astraea_budget_search.argtypes = [C.POINTER(SearchConfig), FITNESS_FN, vp, vp, C.POINTER(C.c_double), vp, vp,
+                                            C.POINTER(C.c_int32)]
+        L.astraea_search_crossover.argtypes = [vp, vp, i32, C.c_int, C.POINTER(C.c_uint64), vp]
+        L.astraea_search_mutate.argtypes = [vp, i32, C.c_double, C.POINTER(C.c_uint64)]
+        L.astraea_search_repair.argtypes = [vp, i32, i64, C.POINTER(C.c_uint64)]
+        for name in ("astraea_budget_search", "astraea_search_crossover", "astraea_search_mutate",
+                     "astraea_search_repair"):
+            getattr(L, name).restype = C.c_int
         for name in ("astraea_score", "astraea_select_topk", "astraea_sparse_attn_fwd",
                      "astraea_sparse_attn_update_fwd", "astraea_scatter_update", "astraea_gather_rows"):
             getattr(L, name).restype = C.c_int
@@ -212,3 +232,54 @@ def astraea_probe_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
     nbytes = src.numel() * src.element_size()
     assert dst.numel() * dst.element_size() == nbytes
     _check(lib().astraea_probe_copy(_p(src), _p(dst), nbytes, _stream()))
+
+
+# ---- token-budget search (host only; numpy int32 arrays, no GPU involved) ----
+
+def _i32(a):
+    import numpy as np
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    return a, a.ctypes.data_as(C.c_void_p)
+
+
+def astraea_search_crossover(parent0, parent1, kind: int, rng_state: int):
+    """Returns (child, new rng state)."""
+    import numpy as np
+    p0, pp0 = _i32(parent0)
+    p1, pp1 = _i32(parent1)
+    child = np.empty_like(p0)
+    st = C.c_uint64(rng_state)
+    _check(lib().astraea_search_crossover(pp0, pp1, p0.size, kind, C.byref(st), child.ctypes.data_as(C.c_void_p)))
+    return child, st.value
+
+
+def astraea_search_mutate(theta, p_mutation: float, rng_state: int):
+    th, p = _i32(theta)
+    th = th.copy()
+    st = C.c_uint64(rng_state)
+    _check(lib().astraea_search_mutate(th.ctypes.data_as(C.c_void_p), th.size, p_mutation, C.byref(st)))
+    return th, st.value
+
+
+def astraea_search_repair(theta, budget_tenths: int, rng_state: int):
+    th, p = _i32(theta)
+    th = th.copy()
+    st = C.c_uint64(rng_state)
+    _check(lib().astraea_search_repair(th.ctypes.data_as(C.c_void_p), th.size, budget_tenths, C.byref(st)))
+    return th, st.value
+
+
+def astraea_budget_search(T: int, budget_tenths: int, population: int, children: int, generations: int,
+                          p_mutation_start: float, p_mutation_final: float, seed: int, fitness):
+    """fitness(list of T levels) -> float, lower is better.  Returns (best schedule, its fitness, final population
+    best first as an int32 array [n, T], their fitness)."""
+    import numpy as np
+    cfg = SearchConfig(T, population, children, generations, budget_tenths, p_mutation_start, p_mutation_final, seed)
+    cb = FITNESS_FN(lambda th, t, _user: float(fitness([th[i] for i in range(t)])))
+    best = np.empty(T, np.int32)
+    pop = np.empty((population, T), np.int32)
+    fit = np.empty(population, np.float64)
+    bf, n = C.c_double(), C.c_int32()
+    _check(lib().astraea_budget_search(C.byref(cfg), cb, None, best.ctypes.data_as(C.c_void_p), C.byref(bf),
+                                       pop.ctypes.data_as(C.c_void_p), fit.ctypes.data_as(C.c_void_p), C.byref(n)))
+    return best, bf.value, pop[:n.value], fit[:n.value]

@@ -140,3 +140,58 @@ def test_search_never_gets_worse_with_more_generations():
     # zero generations: the best of the initial population
     s0 = ob.search(T, B, 16, 10, 0, 0.3, 0.05, 9, f)
     assert s0[1] == min(s0[3]) and len(s0[2]) == 16
+
+
+# ------------------------------------------- the library against the oracle --
+
+from paper_2506_05096_amd import binding as ab   # noqa: E402  (host-only entry points; no GPU is touched)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 99, 2 ** 63 + 5])
+def test_library_operators_match_the_oracle_bit_for_bit(seed):
+    rng = np.random.default_rng(seed % 1000)
+    T = 37
+    p0, p1 = rng.integers(0, 11, T), rng.integers(0, 11, T)
+    for kind, fn in ((ab.CROSSOVER_UNIFORM, ob.crossover_uniform), (ab.CROSSOVER_BLOCK, ob.crossover_block)):
+        r = ob.SplitMix64(seed)
+        want = fn(list(p0), list(p1), r)
+        got, st = ab.astraea_search_crossover(p0, p1, kind, seed)
+        assert list(got) == want and st == r.state
+    for p in (0.0, 0.05, 0.3, 1.0):
+        r = ob.SplitMix64(seed)
+        want = ob.mutate(list(p0), p, r)
+        got, st = ab.astraea_search_mutate(p0, p, seed)
+        assert list(got) == want and st == r.state
+    for budget in (0, 40, 185, 300, 370):
+        r = ob.SplitMix64(seed)
+        want = ob.repair(list(p0), budget, r)
+        got, st = ab.astraea_search_repair(p0, budget, seed)
+        assert list(got) == want and st == r.state
+
+
+@pytest.mark.parametrize("T,budget,pop,children,gens,seed", [(4, 20, 30, 20, 60, 3), (50, 250, 50, 30, 30, 0),
+                                                             (12, 60, 16, 10, 0, 9), (3, 30, 8, 5, 10, 4),
+                                                             (20, 0, 6, 6, 4, 1)])
+def test_library_search_matches_the_oracle_bit_for_bit(T, budget, pop, children, gens, seed):
+    f = _fitness(list(np.linspace(3.0, 0.2, T)))
+    want = ob.search(T, budget, pop, children, gens, 0.3, 0.05, seed, f)
+    got = ab.astraea_budget_search(T, budget, pop, children, gens, 0.3, 0.05, seed, f)
+    assert list(got[0]) == list(want[0]) and got[1] == want[1]
+    assert got[2].tolist() == [list(c) for c in want[2]]
+    assert got[3].tolist() == want[3]
+
+
+def test_library_search_rejects_bad_arguments():
+    f = lambda th: 0.0
+    for kw in (dict(T=0), dict(budget_tenths=-1), dict(budget_tenths=1000), dict(population=0), dict(children=-1),
+               dict(p_mutation_start=1.5), dict(p_mutation_final=float("nan"))):
+        args = dict(T=10, budget_tenths=50, population=5, children=3, generations=2, p_mutation_start=0.3,
+                    p_mutation_final=0.1, seed=1)
+        args.update(kw)
+        with pytest.raises(ab.AstraeaError) as e:
+            ab.astraea_budget_search(fitness=f, **args)
+        assert e.value.status == ab.ERR_INVALID
+    with pytest.raises(ab.AstraeaError):
+        ab.astraea_search_repair([3, 11, 2], 10, 0)          # a level outside 0..10
+    with pytest.raises(ab.AstraeaError):
+        ab.astraea_search_mutate([1, 2], 2.0, 0)
