@@ -315,6 +315,34 @@ def test_attn_bf16_split_items_match_oracle(n, h, k_sel):
     assert np.array_equal(o, o2)
 
 
+@pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 128), (torch.float32, 64)])
+def test_attention_accepts_head_major_and_packed_layouts(dtype, d):
+    """The same numbers laid out three ways must give the same bits: token-major [N, H, d]; head-major
+    [H, N, d] (the layout of the paper's FLOPs appendix) viewed through strides; and one packed [N, 3, H, d]
+    buffer holding Q, K and V side by side (what a fused projection writes)."""
+    n, h, k_sel = 900, 3, 250
+    q, k, v, idx = _attn_case(n, h, d, k_sel, dtype, seed=77)
+    scale = 1.0 / math.sqrt(d)
+    wsb = ab.workspace_bytes(ab.OP_SPARSE_ATTN, n, k_sel, h, d)
+    ws = torch.empty(max(wsb, 1), dtype=torch.uint8, device=DEV) if wsb else None
+
+    def run(qq, kk, vv):
+        o = torch.full((k_sel, h, d), float("nan"), dtype=dtype, device=DEV)
+        ab.astraea_sparse_attn_fwd(qq, kk, vv, idx.to(DEV), k_sel, o, scale, workspace=ws)
+        _sync()
+        return to_np(o)
+
+    base = run(q.to(DEV), k.to(DEV), v.to(DEV))
+    hm = [t.permute(1, 0, 2).contiguous().to(DEV).permute(1, 0, 2) for t in (q, k, v)]       # [H, N, d] storage
+    assert hm[0].stride(0) == d and hm[0].stride(1) == n * d
+    assert np.array_equal(run(*hm), base)
+    packed = torch.stack([q, k, v], dim=1).contiguous().to(DEV)                               # [N, 3, H, d]
+    assert np.array_equal(run(packed[:, 0], packed[:, 1], packed[:, 2]), base)
+    eo, _ = oracle.sparse_attn(to_np(q), to_np(k), to_np(v), idx.numpy(), scale)
+    got = as_f64(base)
+    assert (np.max(np.abs(got - eo)) <= 1e-4) if dtype == torch.float32 else (_rel_l2(got, eo) <= 1e-2)
+
+
 @pytest.mark.parametrize("dtype,d,n_ctx,k_sel", [(torch.bfloat16, 128, 77, 1000), (torch.bfloat16, 128, 256, 5000),
                                                   (torch.float32, 64, 120, 700)])
 def test_cross_attention_of_selected_rows(dtype, d, n_ctx, k_sel):
