@@ -79,3 +79,53 @@ def test_block_budget_zero_changes_nothing():
     torch.cuda.synchronize()
     for k_ in t:
         assert torch.equal(t[k_], before[k_]), k_
+
+
+def test_block_at_the_headline_size_on_sampled_rows():
+    """The block as bench.py runs it: N=118800, H=24, d=128, 30 % budget (k=35640), feature width 3072, MLP width
+    12288.  The oracle cannot recompute all of it, but rows are independent: selection is checked in full and bit for
+    bit, every stage on a sample of selected rows (first and last rows, rows on both sides of tile edges, random
+    ones), each stage from the GPU's own output of the stage before."""
+    from paper_2506_05096_amd import synth
+    w = synth.WORKLOADS["cfg3"]
+    n, H, D, E, hid = w.N, w.H, w.D, w.H * w.D, 4 * w.H * w.D
+    t = synth.make_layer_inputs(w, seed=0, device=DEV)
+    g = torch.Generator(device=DEV).manual_seed(77)
+    mk = lambda o, i: (torch.randn(o, i, device=DEV, generator=g) * i ** -0.5).bfloat16()
+    wts = {"wq": mk(E, E), "wk": mk(E, E), "wv": mk(E, E), "wo": mk(E, E), "w1": mk(hid, E), "w2": mk(E, hid),
+           "bq": (torch.randn(E, device=DEV, generator=g) * 0.1).bfloat16(),
+           "b1": (torch.randn(hid, device=DEV, generator=g) * 0.1).bfloat16()}
+    tt = {"x_in": t["x_cur"], "x_prev": t["x_prev"], "k_cache": t["k_cache"], "v_cache": t["v_cache"],
+          "out_cache": t["out_cache"]}
+    before = {k_: to_np(tt[k_]).reshape(n, E).copy() for k_ in ("k_cache", "v_cache", "out_cache")}
+    x_in, x_prev = to_np(tt["x_in"]), to_np(tt["x_prev"])
+    hw = {k_: to_np(v) for k_, v in wts.items()}
+    blk = TokenSparseBlock(n, H, D, wts, device=DEV)
+    k = blk.budget_to_k(30)
+    blk.run(tt, k)
+    torch.cuda.synchronize()
+
+    e_idx, e_rem, _ = oracle.topk(oracle.score(x_in, x_prev, oracle.DELTA_L2), k)
+    assert np.array_equal(blk.idx_sel[:k].cpu().numpy(), e_idx)
+    rng = np.random.default_rng(0)
+    rows = np.unique(np.concatenate([[0, 1, 63, 64, 255, 256, 257, k - 257, k - 256, k - 2, k - 1],
+                                     rng.integers(0, k, 13)]))
+    tok = e_idx[rows]
+    kc, vc, out = (to_np(tt[k_]).reshape(n, E) for k_ in ("k_cache", "v_cache", "out_cache"))
+    for name, arr in (("k_cache", kc), ("v_cache", vc), ("out_cache", out)):
+        assert np.array_equal(arr[e_rem], before[name][e_rem]), name                 # the others keep their cached rows
+    xs = x_in[tok]
+    q_gpu = to_np(blk.q_sel.view(n, E)[:k])[rows]
+    assert _rel(bf16_bits_to_f64(q_gpu), oracle.sparse_linear(xs, hw["wq"], None, bias=hw["bq"], x_is_compact=True)) <= 1e-2
+    assert _rel(bf16_bits_to_f64(kc[tok]), oracle.sparse_linear(xs, hw["wk"], None, x_is_compact=True)) <= 1e-2
+    assert _rel(bf16_bits_to_f64(vc[tok]), oracle.sparse_linear(xs, hw["wv"], None, x_is_compact=True)) <= 1e-2
+    o64, _ = oracle.sparse_attn(q_gpu.reshape(len(rows), H, D), kc.reshape(n, H, D), vc.reshape(n, H, D), None,
+                                1.0 / math.sqrt(D), q_is_compact=True)
+    o_gpu = to_np(blk.o_sel.view(n, E)[:k])[rows]
+    assert _rel(bf16_bits_to_f64(o_gpu), o64.reshape(len(rows), E)) <= 1e-2
+    h_gpu = to_np(blk.h_sel[:k])[rows]
+    assert _rel(bf16_bits_to_f64(h_gpu), oracle.sparse_linear(o_gpu, hw["wo"], None, x_is_compact=True)) <= 1e-2
+    m_gpu = to_np(blk.m_sel[:k])[rows]
+    ref = oracle.sparse_linear(h_gpu, hw["w1"], None, bias=hw["b1"], act=oracle.ACT_GELU_TANH, x_is_compact=True)
+    assert _rel(bf16_bits_to_f64(m_gpu), ref) <= 1e-2
+    assert _rel(bf16_bits_to_f64(out[tok]), oracle.sparse_linear(m_gpu, hw["w2"], None, x_is_compact=True)) <= 1e-2
