@@ -18,8 +18,9 @@
 //  * the contraction advances in steps of 64; the two 32 KiB tiles of a step go from global memory
 //    straight into LDS (global_load_lds_dwordx4, per-lane addresses, so the row gather costs nothing),
 //    double buffered, 16-byte chunks XOR-swizzled inside each 128-byte row against bank conflicts.
-//    The copy instructions of the next step go out between the first MFMAs of the current one, and
-//    a 4-byte load per row touches the lines of three steps ahead so that the copies hit in L2.
+//    The second wave of each SIMD issues all copy instructions of the next step while it waits for the
+//    matrix pipe, and a 4-byte load per row touches the lines of three steps ahead so that the copies
+//    hit in L2.
 //  * workgroup ids are mapped so that the 32 workgroups resident on one XCD form an 8 x 4 block of
 //    tiles: they stream 8 row tiles and 4 weight tiles through that XCD's L2 instead of 32 + 32.
 #include "common.h"
@@ -42,7 +43,8 @@ constexpr int kTileBytes = 256 * kRowBytes;          // 32 KiB
 constexpr int kStageBytes = 2 * kTileBytes;          // w tile, then x tile
 constexpr int kWaves = 8;                // 8: two per SIMD, 128 features x 64 tokens each; 4: one per SIMD, 128 x 128 each
 constexpr int kTb = 16 / kWaves;         // 32-token MFMA blocks per wave
-constexpr int kCopies = 32 / kWaves;     // 1 KiB copy instructions per wave and tile
+constexpr int kCopyWaves = kWaves / 2;   // the waves that issue the tile copies (the second wave of each SIMD)
+constexpr int kCopies = 32 / kCopyWaves; // 1 KiB copy instructions per copying wave and tile
 constexpr int kNumXcd = 8;
 constexpr int kSbM = 8, kSbN = 4;        // tiles of one XCD round: 8 token tiles x 4 feature tiles
 
@@ -117,16 +119,24 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void linear_bf16_kernel(LinearArg
     const int wn = wave & 1, wm = wave >> 1;          // this wave's 128 features and 32*kTb tokens of the tile
     const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
 
-    // ---- tile copies.  One instruction fills 1 KiB = 8 rows of a tile; wave w issues instructions
-    // w, w+4, ..., w+28 of each tile.  Lane l serves row 8*i + l/8 and the physical chunk l%8, which
-    // holds logical chunk (l%8) ^ ((row/2)%8); for the rows of one wave that is the same in all 8
-    // instructions, so a lane's byte offset inside its rows is fixed.
+    // ---- tile copies.  The two waves of a SIMD take the matrix pipe one after the other, not cycle by
+    // cycle: the first wave (made so by its raised priority) runs its MFMAs of a step while the second
+    // waits for the pipe.  The memory pipe accepts a 1 KiB copy instruction only every ~16 clocks per CU,
+    // so issuing the 64 of a step stalls whoever does it; the second waves do all of it, in the time
+    // they would spend waiting anyway, and the first waves start their MFMAs right after the barrier.
+    // One instruction fills 8 rows of a tile; copying wave c = wave - 4 issues instructions c, c+4, ...,
+    // c+28 of each tile.  Lane l serves row 8*i + l/8 and the physical chunk l%8, which holds logical
+    // chunk (l%8) ^ ((row/2)%8); for the rows of one wave that is the same in all 8 instructions, so a
+    // lane's byte offset inside its rows is fixed.
+    const bool copier = wave >= kCopyWaves;
+    const int cw = wave & (kCopyWaves - 1);
+    if (!copier) __builtin_amdgcn_s_setprio(1);
     const int d_row = lane >> 3;
-    const int lchunk = (lane & 7) ^ ((4 * (wave & 1) + (lane >> 4)) & 7);
+    const int lchunk = (lane & 7) ^ ((4 * (cw & 1) + (lane >> 4)) & 7);
     uint32_t woff[kCopies], xoff[kCopies];   // byte offsets of this lane's rows from w and x
 #pragma unroll
     for (int t = 0; t < kCopies; ++t) {
-        const int r = 8 * (wave + kWaves * t) + d_row;
+        const int r = 8 * (cw + kCopyWaves * t) + d_row;
         int n = n0 + r;                  // rows past the end re-read the last one; they are never stored
         if (n > a.c_out - 1) n = a.c_out - 1;
         woff[t] = (uint32_t)n * (uint32_t)a.c_in * 2u + (uint32_t)lchunk * 16u;
@@ -148,7 +158,7 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void linear_bf16_kernel(LinearArg
     // touching them kPrefetch steps ahead lets the tile copies hit in L2.
     uint32_t pf_w, pf_x;
     {
-        const int r = 8 * (wave + kWaves * ((lane >> 3) % kCopies)) + (lane & 7);
+        const int r = 8 * (cw + kCopyWaves * ((lane >> 3) % kCopies)) + (lane & 7);
         int n = n0 + r;
         if (n > a.c_out - 1) n = a.c_out - 1;
         pf_w = (uint32_t)n * (uint32_t)a.c_in * 2u;
@@ -161,10 +171,10 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void linear_bf16_kernel(LinearArg
     uint32_t sink_w = 0, sink_x = 0;
     constexpr int kPrefetch = 3;
     auto dma_w = [&](int t, int kstep, uint32_t stage) __attribute__((always_inline)) {
-        dma16(wg + (int64_t)kstep * kRowBytes, woff[t], lds0 + stage + (wave + kWaves * t) * 1024);
+        dma16(wg + (int64_t)kstep * kRowBytes, woff[t], lds0 + stage + (cw + kCopyWaves * t) * 1024);
     };
     auto dma_x = [&](int t, int kstep, uint32_t stage) __attribute__((always_inline)) {
-        dma16(xg + (int64_t)kstep * kRowBytes, xoff[t], lds0 + stage + kTileBytes + (wave + kWaves * t) * 1024);
+        dma16(xg + (int64_t)kstep * kRowBytes, xoff[t], lds0 + stage + kTileBytes + (cw + kCopyWaves * t) * 1024);
     };
 
     // ---- fragment addresses: row 32*block + qc of this wave's half, logical chunk 2*s + hf of k-step s
@@ -186,15 +196,17 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void linear_bf16_kernel(LinearArg
 
     const int nk = a.c_in / kBk;
     // prologue: first stage
+    if (copier) {
 #pragma unroll
-    for (int t = 0; t < kCopies; ++t) {
-        dma_w(t, 0, 0);
-        dma_x(t, 0, 0);
-    }
-    for (int p = 1; p < kPrefetch; ++p) {
-        const int kp = p < nk ? p : nk - 1;
-        touch_line(wg + (int64_t)kp * kRowBytes, pf_w, sink_w);
-        touch_line(xg + (int64_t)kp * kRowBytes, pf_x, sink_x);
+        for (int t = 0; t < kCopies; ++t) {
+            dma_w(t, 0, 0);
+            dma_x(t, 0, 0);
+        }
+        for (int p = 1; p < kPrefetch; ++p) {
+            const int kp = p < nk ? p : nk - 1;
+            touch_line(wg + (int64_t)kp * kRowBytes, pf_w, sink_w);
+            touch_line(xg + (int64_t)kp * kRowBytes, pf_x, sink_x);
+        }
     }
     wait_dma();
     __builtin_amdgcn_s_barrier();
@@ -205,6 +217,17 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void linear_bf16_kernel(LinearArg
         // rather than branch around every copy
         const int kn = kk + 1 < nk ? kk + 1 : kk;
         const int kp = kk + kPrefetch < nk ? kk + kPrefetch : nk - 1;
+        if (copier) {
+            // all of the next step's copies, then the warm-up loads (after the copies, so that waiting for
+            // the copies leaves them pending)
+#pragma unroll
+            for (int t = 0; t < kCopies; ++t) {
+                dma_w(t, kn, next_stage);
+                dma_x(t, kn, next_stage);
+            }
+            touch_line(wg + (int64_t)kp * kRowBytes, pf_w, sink_w);
+            touch_line(xg + (int64_t)kp * kRowBytes, pf_x, sink_x);
+        }
         bf16x8 wf[2][4], xf[2][kTb];
 #pragma unroll
         for (int i = 0; i < 4; ++i) wf[0][i] = lds_read_b128(wa[0] + i * 32 * kRowBytes);
@@ -221,16 +244,6 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void linear_bf16_kernel(LinearArg
             }
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                // the next step's copies go out during the first half of this one, two per four MFMAs, so that
-                // they have landed when the step ends
-                if (4 * s + i < kCopies) {
-                    dma_w(4 * s + i, kn, next_stage);
-                    dma_x(4 * s + i, kn, next_stage);
-                }
-                if (s == 2 && i == 0) {          // after the copies, so that waiting for those leaves these pending
-                    touch_line(wg + (int64_t)kp * kRowBytes, pf_w, sink_w);
-                    touch_line(xg + (int64_t)kp * kRowBytes, pf_x, sink_x);
-                }
 #pragma unroll
                 for (int j = 0; j < kTb; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[cur][i], xf[cur][j], acc[i][j], 0, 0, 0);
