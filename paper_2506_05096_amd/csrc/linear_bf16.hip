@@ -230,23 +230,37 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void linear_bf16_kernel(LinearArg
         }
         bf16x8 wf[2][4], xf[2][kTb];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) wf[0][i] = lds_read_b128(wa[0] + i * 32 * kRowBytes);
-#pragma unroll
         for (int j = 0; j < kTb; ++j) xf[0][j] = lds_read_b128(xa[0] + j * 32 * kRowBytes);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) wf[0][i] = lds_read_b128(wa[0] + i * 32 * kRowBytes);
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             const int cur = s & 1, nxt = cur ^ 1;
             if (s < 3) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) wf[nxt][i] = lds_read_b128(wa[s + 1] + i * 32 * kRowBytes);
+                // x fragments first: every MFMA of the quarter needs them, the w fragments are needed one by one
 #pragma unroll
                 for (int j = 0; j < kTb; ++j) xf[nxt][j] = lds_read_b128(xa[s + 1] + j * 32 * kRowBytes);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) wf[nxt][i] = lds_read_b128(wa[s + 1] + i * 32 * kRowBytes);
             }
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
 #pragma unroll
                 for (int j = 0; j < kTb; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[cur][i], xf[cur][j], acc[i][j], 0, 0, 0);
+            }
+            // order inside the quarter: each fragment read of the next quarter goes out behind one MFMA of
+            // this one, i.e. a quarter ahead of its use (left alone, the scheduler sinks the reads to just
+            // before the MFMAs that need them and the wave waits out the LDS latency several times per quarter)
+            if (s < 3) {
+#pragma unroll
+                for (int r = 0; r < 4 + kTb; ++r) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, 4 * kTb - (4 + kTb), 0);
+            } else {
+                __builtin_amdgcn_sched_group_barrier(0x008, 4 * kTb, 0);
             }
         }
         // the next step's tiles are complete and this step's are no longer read: swap stages
