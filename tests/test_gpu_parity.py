@@ -223,7 +223,8 @@ def _rel_l2(a, b):
 
 
 @pytest.mark.parametrize("n,h,k_sel,bias", [(1000, 3, 333, 0.0), (64, 1, 64, 0.0), (129, 2, 1, 0.0),
-                                            (2500, 2, 130, 0.5), (4096, 2, 128, 0.0)])
+                                            (2500, 2, 130, 0.5), (4096, 2, 128, 0.0),
+                                            (1, 1, 1, 0.0), (1, 24, 1, 0.0), (63, 2, 63, 0.0), (191, 1, 7, 0.0)])
 def test_attn_bf16_matches_oracle(n, h, k_sel, bias):
     d = 128
     q, k, v, idx = _attn_case(n, h, d, k_sel, torch.bfloat16, seed=n + 1, bias_std=bias)
