@@ -150,11 +150,12 @@ def token_sparse_block(torch, ab, w, t, k, reps=5):
     E, hid, dev = w.H * w.D, 4 * w.H * w.D, t["q"].device
     g = torch.Generator(device=dev).manual_seed(4242)
     mk = lambda o, i: (torch.randn(o, i, device=dev, generator=g) * i ** -0.5).bfloat16()
-    weights = {"wq": mk(E, E), "wk": mk(E, E), "wv": mk(E, E), "wo": mk(E, E), "w1": mk(hid, E), "w2": mk(E, hid),
+    weights = {"wqkv": mk(3 * E, E), "wo": mk(E, E), "w1": mk(hid, E), "w2": mk(E, hid),
                "b1": torch.zeros(hid, dtype=torch.bfloat16, device=dev), "b2": torch.zeros(E, dtype=torch.bfloat16, device=dev)}
     blk = TokenSparseBlock(w.N, w.H, w.D, weights, device=dev)
-    tt = {"x_in": t["x_cur"], "x_prev": t["x_prev"], "k_cache": t["k_cache"], "v_cache": t["v_cache"],
-          "out_cache": t["out_cache"]}
+    # packed [N, 3, H, D] cache: Q, K and V of a token side by side, written by one stacked projection
+    tt = {"x_in": t["x_cur"], "x_prev": t["x_prev"], "out_cache": t["out_cache"],
+          "qkv_cache": torch.stack([t["q"], t["k_cache"], t["v_cache"]], dim=1).contiguous()}
     if tt["x_in"].shape[1] != E:
         return {"skipped": "feature width of this workload is not H*D"}
     blk.run(tt, k)
@@ -182,8 +183,9 @@ def token_sparse_block(torch, ab, w, t, k, reps=5):
             "linear_TFLOPs": (fl_qkv + fl_rest) / lin_ms / 1e9,
             "linear_frac_of_mfma_peak": (fl_qkv + fl_rest) / lin_ms / 1e9 / PEAK_TFLOPS["bf16"],
             "linear_flops": fl_qkv + fl_rest,
-            "what": "score + top-k + 3 projections of the selected rows (K/V written into the caches) + attention + "
-                    "output projection + 2 MLP layers (the last writes the cached block output); hidden width 4*H*D"}
+            "what": "score + top-k + stacked Q/K/V projection of the selected rows written into a packed cache + "
+                    "attention + output projection + 2 MLP layers (the last writes the cached block output); "
+                    "hidden width 4*H*D"}
 
 
 def main() -> int:

@@ -129,3 +129,35 @@ def test_block_at_the_headline_size_on_sampled_rows():
     ref = oracle.sparse_linear(h_gpu, hw["w1"], None, bias=hw["b1"], act=oracle.ACT_GELU_TANH, x_is_compact=True)
     assert _rel(bf16_bits_to_f64(m_gpu), ref) <= 1e-2
     assert _rel(bf16_bits_to_f64(out[tok]), oracle.sparse_linear(m_gpu, hw["w2"], None, x_is_compact=True)) <= 1e-2
+
+
+def test_block_with_packed_qkv_cache_equals_the_three_projection_form():
+    """One stacked projection into a packed [N, 3, H, D] cache must give the bits of the three separate ones."""
+    n, H, D = 1100, 2, 128
+    E, hid = H * D, 4 * H * D
+    g = torch.Generator().manual_seed(5)
+    rnd = lambda *s, sc=1.0: (torch.randn(*s, generator=g) * sc).bfloat16().to(DEV)
+    w = {"wq": rnd(E, E, sc=E ** -0.5), "wk": rnd(E, E, sc=E ** -0.5), "wv": rnd(E, E, sc=E ** -0.5),
+         "wo": rnd(E, E, sc=E ** -0.5), "w1": rnd(hid, E, sc=E ** -0.5), "w2": rnd(E, hid, sc=hid ** -0.5)}
+    x_prev = rnd(n, E)
+    base = {"x_prev": x_prev, "x_in": (x_prev.float() + 0.1 * torch.randn(n, E, generator=g).to(DEV)).bfloat16(),
+            "k_cache": rnd(n, H, D), "v_cache": rnd(n, H, D), "out_cache": rnd(n, E)}
+    ta = {k_: v.clone() for k_, v in base.items()}
+    blk = TokenSparseBlock(n, H, D, w, device=DEV)
+    k = blk.budget_to_k(40)
+    blk.run(ta, k)
+    wp = dict(w, wqkv=torch.cat([w["wq"], w["wk"], w["wv"]], dim=0).contiguous())
+    q_old = rnd(n, H, D)
+    tb = {k_: v.clone() for k_, v in base.items() if k_ not in ("k_cache", "v_cache")}
+    tb["qkv_cache"] = torch.stack([q_old, base["k_cache"], base["v_cache"]], dim=1).contiguous()
+    blk2 = TokenSparseBlock(n, H, D, wp, device=DEV)
+    blk2.run(tb, k)
+    torch.cuda.synchronize()
+    idx = blk.idx_sel[:k].long()
+    assert torch.equal(blk.idx_sel[:k], blk2.idx_sel[:k])
+    assert torch.equal(tb["qkv_cache"][:, 1], ta["k_cache"]) and torch.equal(tb["qkv_cache"][:, 2], ta["v_cache"])
+    assert torch.equal(tb["qkv_cache"][idx, 0], blk.q_sel[:k])                 # fresh Q of the selected tokens
+    rest = torch.ones(n, dtype=torch.bool, device=DEV)
+    rest[idx] = False
+    assert torch.equal(tb["qkv_cache"][rest, 0], q_old[rest])                  # the others keep what they had
+    assert torch.equal(tb["out_cache"], ta["out_cache"])
