@@ -249,16 +249,17 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
         }
     };
 
-    // ---- LDS read addresses of the current parity (the parity bit is flipped in place every tile)
+    // ---- LDS read offsets (relative to the array) of the current parity; the parity bit is flipped in
+    // place every tile, and the array's base is added where the offsets are used
     // K fragment (kb, s): row 32*kb + qc, logical chunk 2*s + hf; kb is an immediate offset
     uint32_t ka[D / 16];
 #pragma unroll
-    for (int s = 0; s < D / 16; ++s) ka[s] = lds0 + qc * kRowBytes + (((2 * s + hf) ^ (qc & 15)) << 4);
+    for (int s = 0; s < D / 16; ++s) ka[s] = qc * kRowBytes + (((2 * s + hf) ^ (qc & 15)) << 4);
     // V^T fragment (tt, b): row d = 32*b + qc (128-byte rows), logical chunk 2*tt + hf; b is an immediate
     uint32_t va[4];
 #pragma unroll
     for (int tt = 0; tt < 4; ++tt)
-        va[tt] = lds0 + kTileBytes + qc * 128 + (((2 * tt + hf) ^ ((qc >> 1) & 7)) << 4);
+        va[tt] = kTileBytes + qc * 128 + (((2 * tt + hf) ^ ((qc >> 1) & 7)) << 4);
 
     floatx16 sacc[2];          // S^T of the current tile (two blocks of 32 keys)
     uint32_t pw[16];           // P^T as bf16 pairs: pw[8*kb + i] = registers 2i, 2i+1 of block kb
@@ -322,7 +323,7 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
         constexpr bool WITH_QK = decltype(qk_tag)::value;
         bf16x8 vf[16], kf[16];
 #pragma unroll
-        for (int u = 0; u < kAhead; ++u) vf[u] = lds_read_b128(va[u >> 2] + (u & 3) * 32 * 128);
+        for (int u = 0; u < kAhead; ++u) vf[u] = lds_read_b128(lds0 + va[u >> 2] + (u & 3) * 32 * 128);
 #pragma unroll
         for (int u = 0; u < 16; ++u) {
             const int tt = u >> 2, b = u & 3;
@@ -330,9 +331,9 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
             oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[u], __builtin_bit_cast(bf16x8, p4), oacc[b], 0, 0, 0);
             const int n = u + kAhead;
             if (n < 16)
-                vf[n] = lds_read_b128(va[n >> 2] + (n & 3) * 32 * 128);
+                vf[n] = lds_read_b128(lds0 + va[n >> 2] + (n & 3) * 32 * 128);
             else if (WITH_QK)
-                kf[n - 16] = lds_read_b128(ka[(n - 16) & 7] + ((n - 16) >> 3) * 32 * kRowBytes);
+                kf[n - 16] = lds_read_b128(lds0 + ka[(n - 16) & 7] + ((n - 16) >> 3) * 32 * kRowBytes);
         }
         if (WITH_QK) {
 #pragma unroll
@@ -344,7 +345,7 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
             for (int u = 0; u < 16; ++u) {
                 sacc[u >> 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[u], qf[u & 7], sacc[u >> 3], 0, 0, 0);
                 const int n = u + kAhead;
-                if (n < 16) kf[n] = lds_read_b128(ka[n & 7] + (n >> 3) * 32 * kRowBytes);
+                if (n < 16) kf[n] = lds_read_b128(lds0 + ka[n & 7] + (n >> 3) * 32 * kRowBytes);
             }
         }
         SGB(DSR, kAhead);
@@ -365,7 +366,7 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
 #pragma unroll
         for (int u = 0; u < 16; ++u)
             sacc[u >> 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                lds_read_b128(ka[u & 7] + (u >> 3) * 32 * kRowBytes), qf[u & 7], sacc[u >> 3], 0, 0, 0);
+                lds_read_b128(lds0 + ka[u & 7] + (u >> 3) * 32 * kRowBytes), qf[u & 7], sacc[u >> 3], 0, 0, 0);
     };
     // the asm pins keep the address updates where they are written (in a VALU phase)
     auto flip_k = [&]() __attribute__((always_inline)) {

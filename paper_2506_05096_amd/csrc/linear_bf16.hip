@@ -98,8 +98,7 @@ struct LinearArgs {
 
 __global__ __launch_bounds__(kWaves *kWave, 1) void linear_bf16_kernel(LinearArgs a)
 {
-    // [stage][w tile | x tile]; the only LDS object of the kernel, so it starts at LDS address 0, which
-    // the stage flips (XOR) rely on.
+    // [stage][w tile | x tile].  Stage flips XOR offsets relative to this array, never absolute addresses.
     constexpr int kPitch = 272;          // epilogue staging: 128 features of a token, padded
     constexpr int kEpiBytes = kWaves * 64 * kPitch;   // every wave stages 64 tokens at a time
     __shared__ __attribute__((aligned(1024))) char lds[2 * kStageBytes > kEpiBytes ? 2 * kStageBytes : kEpiBytes];
@@ -177,13 +176,13 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void linear_bf16_kernel(LinearArg
         dma16(xg + (int64_t)kstep * kRowBytes, xoff[t], lds0 + stage + kTileBytes + (cw + kCopyWaves * t) * 1024);
     };
 
-    // ---- fragment addresses: row 32*block + qc of this wave's half, logical chunk 2*s + hf of k-step s
+    // ---- fragment offsets inside the array: row 32*block + qc of this wave's half, logical chunk 2*s + hf of k-step s
     uint32_t wa[4], xa[4];
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
         const uint32_t sw = (uint32_t)(((2 * s + hf) ^ ((qc >> 1) & 7)) << 4);
-        wa[s] = lds0 + (wn * 128 + qc) * kRowBytes + sw;
-        xa[s] = lds0 + kTileBytes + (wm * 32 * kTb + qc) * kRowBytes + sw;
+        wa[s] = (wn * 128 + qc) * kRowBytes + sw;
+        xa[s] = kTileBytes + (wm * 32 * kTb + qc) * kRowBytes + sw;
     }
 
     floatx16 acc[4][kTb];                // [feature block][token block]
@@ -230,18 +229,18 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void linear_bf16_kernel(LinearArg
         }
         bf16x8 wf[2][4], xf[2][kTb];
 #pragma unroll
-        for (int j = 0; j < kTb; ++j) xf[0][j] = lds_read_b128(xa[0] + j * 32 * kRowBytes);
+        for (int j = 0; j < kTb; ++j) xf[0][j] = lds_read_b128(lds0 + xa[0] + j * 32 * kRowBytes);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) wf[0][i] = lds_read_b128(wa[0] + i * 32 * kRowBytes);
+        for (int i = 0; i < 4; ++i) wf[0][i] = lds_read_b128(lds0 + wa[0] + i * 32 * kRowBytes);
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             const int cur = s & 1, nxt = cur ^ 1;
             if (s < 3) {
                 // x fragments first: every MFMA of the quarter needs them, the w fragments are needed one by one
 #pragma unroll
-                for (int j = 0; j < kTb; ++j) xf[nxt][j] = lds_read_b128(xa[s + 1] + j * 32 * kRowBytes);
+                for (int j = 0; j < kTb; ++j) xf[nxt][j] = lds_read_b128(lds0 + xa[s + 1] + j * 32 * kRowBytes);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) wf[nxt][i] = lds_read_b128(wa[s + 1] + i * 32 * kRowBytes);
+                for (int i = 0; i < 4; ++i) wf[nxt][i] = lds_read_b128(lds0 + wa[s + 1] + i * 32 * kRowBytes);
             }
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
