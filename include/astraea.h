@@ -274,6 +274,17 @@ double astraea_attn_flops(int64_t N, int64_t k_sel, int32_t H, int32_t D);
 int astraea_probe_mfma_bf16(int32_t workgroups, int32_t iters, int32_t randomize, float *sink, int64_t sink_elems,
                             double *flops_out, void *stream);
 int astraea_probe_copy(const void *src, void *dst, int64_t bytes, void *stream);
+/*
+ * Kernel timer, also a measurement aid.  astraea_probe_kernel_timer(1) makes every following
+ * astraea_sparse_attn_fwd / astraea_sparse_attn_update_fwd call of this thread record a pair of HIP
+ * events on its stream around its main kernel alone (not the V re-tiling pre-pass, not the merge of
+ * partial results), for up to 64 calls; (0) stops it; either resets the count.  The events are created
+ * on the first enable and kept.  astraea_probe_kernel_count returns how many launches were timed,
+ * astraea_probe_kernel_ms(i, &ms) waits for launch i to finish and returns its duration (host pointer).
+ */
+int astraea_probe_kernel_timer(int enable);
+int32_t astraea_probe_kernel_count(void);
+int astraea_probe_kernel_ms(int32_t index, double *ms_out);
 
 const char *astraea_status_string(int status);
 const char *astraea_last_error(void);

@@ -27,7 +27,8 @@ CROSSOVER_UNIFORM, CROSSOVER_BLOCK = 0, 1
 EXPORTS = (
     "astraea_score", "astraea_select_topk", "astraea_sparse_attn_fwd", "astraea_sparse_attn_update_fwd",
     "astraea_scatter_update", "astraea_gather_rows", "astraea_sparse_linear", "astraea_workspace_bytes", "astraea_budget_to_k", "astraea_attn_flops",
-    "astraea_probe_mfma_bf16", "astraea_probe_copy", "astraea_lse_weight_update",
+    "astraea_probe_mfma_bf16", "astraea_probe_copy", "astraea_probe_kernel_timer", "astraea_probe_kernel_count",
+    "astraea_probe_kernel_ms", "astraea_lse_weight_update",
     "astraea_budget_search", "astraea_search_crossover", "astraea_search_mutate", "astraea_search_repair",
     "astraea_status_string", "astraea_last_error",
 )
@@ -85,6 +86,11 @@ def lib() -> C.CDLL:
         L.astraea_lse_weight_update.restype = C.c_int
         L.astraea_probe_mfma_bf16.argtypes = [i32, i32, i32, vp, i64, C.POINTER(C.c_double), vp]
         L.astraea_probe_copy.argtypes = [vp, vp, i64, vp]
+        L.astraea_probe_kernel_timer.argtypes = [C.c_int]
+        L.astraea_probe_kernel_timer.restype = C.c_int
+        L.astraea_probe_kernel_count.restype = i32
+        L.astraea_probe_kernel_ms.argtypes = [i32, C.POINTER(C.c_double)]
+        L.astraea_probe_kernel_ms.restype = C.c_int
         L.astraea_probe_mfma_bf16.restype = C.c_int
         L.astraea_probe_copy.restype = C.c_int
         L.astraea_budget_search.argtypes = [C.POINTER(SearchConfig), FITNESS_FN, vp, vp, C.POINTER(C.c_double), vp, vp,
@@ -232,6 +238,20 @@ def astraea_probe_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
     nbytes = src.numel() * src.element_size()
     assert dst.numel() * dst.element_size() == nbytes
     _check(lib().astraea_probe_copy(_p(src), _p(dst), nbytes, _stream()))
+
+
+def kernel_timer(enable: bool) -> None:
+    _check(lib().astraea_probe_kernel_timer(1 if enable else 0))
+
+
+def kernel_times_ms():
+    """Durations of the attention main kernels timed since the timer was switched on."""
+    out = []
+    for i in range(lib().astraea_probe_kernel_count()):
+        ms = C.c_double()
+        _check(lib().astraea_probe_kernel_ms(i, C.byref(ms)))
+        out.append(ms.value)
+    return out
 
 
 # ---- token-budget search (host only; numpy int32 arrays, no GPU involved) ----

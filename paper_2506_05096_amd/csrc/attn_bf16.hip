@@ -586,10 +586,12 @@ int launch_attn_bf16_d128(const void *q, const void *k, const void *v, int64_t N
     hipLaunchKernelGGL(transpose_v_kernel, dim3((unsigned)ntiles, (unsigned)H), dim3(256), 0, stream,
                        (const __bf16 *)v, N, kv_stride_n, kv_stride_h, ntiles, vt);
     dim3 grid((unsigned)(slots * kNumXcd)), block(kWaves * kWave);
+    kernel_timer_begin(stream);
     hipLaunchKernelGGL(attn_bf16_kernel, grid, block, 0, stream, (const __bf16 *)q, (const __bf16 *)k,
                        (const char *)vt, N, H, q_stride_n, q_stride_h, kv_stride_n, kv_stride_h, idx_sel, k_sel,
                        q_is_compact, scale * 1.44269504088896340736f, (__bf16 *)o_sel, o_stride_n, o_scatter, lse_sel, sch,
                        partial);
+    kernel_timer_end(stream);
     if (left > 0)
         hipLaunchKernelGGL(merge_partials_kernel, dim3((unsigned)(left * kNumXcd), kBq / 8), dim3(256), 0, stream, partial, sch,
                            H, k_sel, idx_sel, (__bf16 *)o_sel, o_stride_n, o_scatter, lse_sel);

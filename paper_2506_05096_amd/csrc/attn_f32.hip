@@ -159,6 +159,7 @@ int launch_attn_f32(const void *q, const void *k, const void *v, int64_t N, int3
     if (k_sel == 0) return ASTRAEA_OK;
     dim3 grid((unsigned)((k_sel + kBq - 1) / kBq), (unsigned)H), block(kWaves * kWave);
     const float c = scale * 1.44269504088896340736f;
+    kernel_timer_begin(stream);
     if (D == 64)
         hipLaunchKernelGGL(attn_f32_kernel<64>, grid, block, 0, stream, (const float *)q, (const float *)k,
                            (const float *)v, N, H, q_stride_n, q_stride_h, kv_stride_n, kv_stride_h, idx_sel, k_sel,
@@ -167,6 +168,7 @@ int launch_attn_f32(const void *q, const void *k, const void *v, int64_t N, int3
         hipLaunchKernelGGL(attn_f32_kernel<128>, grid, block, 0, stream, (const float *)q, (const float *)k,
                            (const float *)v, N, H, q_stride_n, q_stride_h, kv_stride_n, kv_stride_h, idx_sel, k_sel,
                            q_is_compact, c, (float *)o_sel, o_stride_n, o_scatter, lse_sel);
+    kernel_timer_end(stream);
     return check_launch("astraea_sparse_attn_fwd(f32)");
 }
 

@@ -15,6 +15,11 @@ int fail(int status, const char *fmt, ...);
 // Checks hipGetLastError() after a launch.
 int check_launch(const char *what);
 
+// Measurement aid: while the kernel timer is on, the attention launchers bracket their main kernel with a
+// pair of HIP events on the caller's stream (astraea_probe_kernel_timer / astraea_probe_kernel_ms).
+void kernel_timer_begin(hipStream_t stream);
+void kernel_timer_end(hipStream_t stream);
+
 // ---- launchers (each enqueues on `stream`, arguments already validated) ----
 int launch_score(const void *x_cur, const void *x_prev, astraea_dtype dt, int64_t N, int64_t C, int64_t row_stride,
                  astraea_delta_mode mode, const float *lse_weight, const int32_t *skip_count,

@@ -83,3 +83,68 @@ int astraea_probe_copy(const void *src, void *dst, int64_t bytes, void *stream)
 }
 
 }  // extern "C"
+
+// ---- kernel timer: events around the attention's main kernel, kept per thread ----
+namespace astraea {
+namespace {
+constexpr int kTimerSlots = 64;
+struct KernelTimer {
+    bool enabled = false;
+    bool open = false;       // a begin without its end yet
+    int count = 0;           // completed pairs
+    bool created = false;
+    hipEvent_t ev[kTimerSlots][2];
+};
+thread_local KernelTimer g_timer;
+}  // namespace
+
+void kernel_timer_begin(hipStream_t stream)
+{
+    KernelTimer &t = g_timer;
+    if (!t.enabled || t.count >= kTimerSlots) return;
+    if (hipEventRecord(t.ev[t.count][0], stream) == hipSuccess) t.open = true;
+}
+void kernel_timer_end(hipStream_t stream)
+{
+    KernelTimer &t = g_timer;
+    if (!t.open) return;
+    t.open = false;
+    if (hipEventRecord(t.ev[t.count][1], stream) == hipSuccess) ++t.count;
+}
+}  // namespace astraea
+
+extern "C" int astraea_probe_kernel_timer(int enable)
+{
+    using namespace astraea;
+    KernelTimer &t = g_timer;
+    if (enable && !t.created) {
+        for (int i = 0; i < kTimerSlots; ++i)
+            for (int j = 0; j < 2; ++j)
+                if (hipEventCreate(&t.ev[i][j]) != hipSuccess)
+                    return fail(ASTRAEA_ERR_HIP, "astraea_probe_kernel_timer: hipEventCreate failed");
+        t.created = true;
+    }
+    t.enabled = enable != 0;
+    t.open = false;
+    t.count = 0;
+    return ASTRAEA_OK;
+}
+
+extern "C" int astraea_probe_kernel_ms(int32_t index, double *ms_out)
+{
+    using namespace astraea;
+    KernelTimer &t = g_timer;
+    if (!ms_out) return fail(ASTRAEA_ERR_INVALID, "astraea_probe_kernel_ms: NULL output");
+    if (index < 0 || index >= t.count)
+        return fail(ASTRAEA_ERR_INVALID, "astraea_probe_kernel_ms: %d launches were timed, index %d asked", t.count,
+                    (int)index);
+    if (hipEventSynchronize(t.ev[index][1]) != hipSuccess)
+        return fail(ASTRAEA_ERR_HIP, "astraea_probe_kernel_ms: hipEventSynchronize failed");
+    float ms = 0.0f;
+    if (hipEventElapsedTime(&ms, t.ev[index][0], t.ev[index][1]) != hipSuccess)
+        return fail(ASTRAEA_ERR_HIP, "astraea_probe_kernel_ms: hipEventElapsedTime failed");
+    *ms_out = (double)ms;
+    return ASTRAEA_OK;
+}
+
+extern "C" int32_t astraea_probe_kernel_count(void) { return astraea::g_timer.count; }

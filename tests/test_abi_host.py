@@ -170,6 +170,16 @@ def test_row_movers_reject_bad_arguments(L):
     assert ga(None, None, ab.F32, 10, 8, 8, 8, None, 0, None) == ab.OK
 
 
+def test_kernel_timer_is_off_by_default_and_rejects_bad_reads(L):
+    ms = C.c_double(-1.0)
+    assert L.astraea_probe_kernel_count() == 0
+    assert L.astraea_probe_kernel_ms(0, C.byref(ms)) == ab.ERR_INVALID
+    assert L.astraea_probe_kernel_ms(-1, C.byref(ms)) == ab.ERR_INVALID
+    assert L.astraea_probe_kernel_ms(0, None) == ab.ERR_INVALID
+    assert ms.value == -1.0
+    assert ab.kernel_times_ms() == []
+
+
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(ab, "_lib", None)
     monkeypatch.setattr(ab, "LIB_PATH", tmp_path / "missing.so")

@@ -413,3 +413,39 @@ def test_attn_update_equals_attention_then_scatter(dtype, n, h, d, k_sel, pad):
         assert np.max(np.abs(got - eo)) <= 1e-4
     else:
         assert _rel_l2(got, eo) <= 1e-2
+
+
+# ------------------------------------------------------------ kernel timer --
+
+@pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 128), (torch.float32, 64)])
+def test_kernel_timer_counts_attention_launches_and_leaves_results_alone(dtype, d):
+    """With the timer on, each attention call adds one timed launch whose duration is positive and no longer than
+    the whole call measured around it; outputs are the bits the untimed call gives; off again, nothing is counted."""
+    n, h, k_sel = 2000, 2, 600
+    q, k, v, idx = _attn_case(n, h, d, k_sel, dtype, seed=17)
+    scale = 1.0 / math.sqrt(d)
+    wsb = ab.workspace_bytes(ab.OP_SPARSE_ATTN, n, k_sel, h, d)
+    ws = torch.empty(max(wsb, 1), dtype=torch.uint8, device=DEV) if wsb else None
+    dq, dk, dv, didx = q.to(DEV), k.to(DEV), v.to(DEV), idx.to(DEV)
+    o0 = torch.empty(k_sel, h, d, dtype=dtype, device=DEV)
+    ab.astraea_sparse_attn_fwd(dq, dk, dv, didx, k_sel, o0, scale, workspace=ws)
+    _sync()
+    ab.kernel_timer(True)
+    try:
+        assert ab.kernel_times_ms() == []
+        o1 = torch.empty_like(o0)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(3):
+            ab.astraea_sparse_attn_fwd(dq, dk, dv, didx, k_sel, o1, scale, workspace=ws)
+        b.record()
+        _sync()
+        ms = ab.kernel_times_ms()
+        assert len(ms) == 3 and all(t > 0.0 for t in ms)
+        assert sum(ms) <= a.elapsed_time(b) * 1.05
+    finally:
+        ab.kernel_timer(False)
+    ab.astraea_sparse_attn_fwd(dq, dk, dv, didx, k_sel, o1, scale, workspace=ws)
+    _sync()
+    assert ab.kernel_times_ms() == []
+    assert np.array_equal(to_np(o0), to_np(o1))
