@@ -102,6 +102,9 @@ void kernel_timer_begin(hipStream_t stream)
 {
     KernelTimer &t = g_timer;
     if (!t.enabled || t.count >= kTimerSlots) return;
+    // under stream capture an event record would become a graph node with no time of its own: skip the launch
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) return;
     if (hipEventRecord(t.ev[t.count][0], stream) == hipSuccess) t.open = true;
 }
 void kernel_timer_end(hipStream_t stream)

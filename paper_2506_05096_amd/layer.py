@@ -183,3 +183,32 @@ class TokenSparseBlock(LayerStep):
         self.step_qkv(t, k)
         self.step_attn(t, k)
         self.step_proj_mlp(t, k)
+
+
+class GraphedStep:
+    """A call chain recorded once as a HIP graph and replayed with one launch.
+
+    Every entry point of the library only enqueues kernels on the caller's stream: it allocates nothing,
+    never waits for the device and records no memset, and k is a host number, so a whole layer-step at a fixed
+    k can be captured.  That pays where the step is short against the cost of launching its seven to ten
+    kernels one by one (small token counts, small budgets); the 50-step schedule of a denoising run needs one
+    graph per distinct budget, at most ten.
+
+    `fn` is any callable that makes the calls (e.g. ``lambda: layer.run(t, k)``); the tensors it touches must
+    stay alive and in place, new inputs are copied into them before a replay.  With `warm` the chain is run
+    once for real before the capture, so that code objects are loaded outside it; that run changes the caches
+    and counters like any step, so pass ``warm=False`` when the same chain has already run in this process
+    and its state must not advance.  Capture and replay use torch's HIP-graph wrapper, on streams of default
+    priority.
+    """
+
+    def __init__(self, fn, warm: bool = True):
+        if warm:
+            fn()
+        torch.cuda.synchronize()
+        self.graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self.graph):
+            fn()
+
+    def replay(self) -> None:
+        self.graph.replay()
