@@ -18,6 +18,11 @@
  *    astraea_last_error() holds a message (thread-local).
  *  - bf16 is the upper half of IEEE binary32; conversions to bf16 round to
  *    nearest even.
+ *  - idx_sel is device data, so the host cannot check it.  It must hold
+ *    distinct indices in [0, N) (what astraea_select_topk writes).  An index
+ *    outside that range never becomes an access outside the buffers: a row
+ *    read through it reads some valid row instead, a row written through it
+ *    is dropped; no error is reported.  Duplicates make the writes race.
  */
 #ifndef ASTRAEA_H
 #define ASTRAEA_H

@@ -173,7 +173,7 @@ int astraea_sparse_linear(const void *x, const void *w, const void *bias, astrae
     if (((uintptr_t)x | (uintptr_t)w | (uintptr_t)y | (uintptr_t)bias) % 16 != 0)
         return fail(ASTRAEA_ERR_INVALID, "%s: x, w, bias and y must be 16-byte aligned", fn);
     if ((uintptr_t)idx_sel % 4 != 0) return fail(ASTRAEA_ERR_INVALID, "%s: idx_sel must be 4-byte aligned", fn);
-    return launch_linear_bf16(x, w, bias, y, idx_sel, k_sel, (int32_t)c_in, (int32_t)c_out, x_row_stride, y_row_stride,
+    return launch_linear_bf16(x, w, bias, y, idx_sel, k_sel, N, (int32_t)c_in, (int32_t)c_out, x_row_stride, y_row_stride,
                               x_is_compact ? 0 : 1, y_is_compact ? 0 : 1, (int)act, (hipStream_t)stream);
 }
 
@@ -202,7 +202,7 @@ int astraea_scatter_update(void *cache, const void *src, astraea_dtype dt, int64
     if (rc != ASTRAEA_OK || k_sel == 0) return rc;
     const int64_t es = (int64_t)esize(dt);
     return launch_move_rows(cache, src, row_elems * es, cache_row_stride * es, src_row_stride * es, idx_sel, k_sel,
-                            true, src_is_full != 0, (hipStream_t)stream);
+                            N, true, src_is_full != 0, (hipStream_t)stream);
 }
 
 int astraea_gather_rows(const void *src, void *dst, astraea_dtype dt, int64_t N, int64_t row_elems,
@@ -213,8 +213,8 @@ int astraea_gather_rows(const void *src, void *dst, astraea_dtype dt, int64_t N,
                         k_sel);
     if (rc != ASTRAEA_OK || k_sel == 0) return rc;
     const int64_t es = (int64_t)esize(dt);
-    return launch_move_rows(dst, src, row_elems * es, dst_row_stride * es, src_row_stride * es, idx_sel, k_sel, false,
-                            true, (hipStream_t)stream);
+    return launch_move_rows(dst, src, row_elems * es, dst_row_stride * es, src_row_stride * es, idx_sel, k_sel, N,
+                            false, true, (hipStream_t)stream);
 }
 
 int astraea_lse_weight_update(const float *lse_sel, int32_t H, int64_t N, const int32_t *idx_sel, int64_t k_sel,

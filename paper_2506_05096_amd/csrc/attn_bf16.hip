@@ -196,7 +196,11 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
     // ---- Q fragment: lane holds query column qc, head-dim 16*s + 8*hf + 0..7 (B operand of K Q^T)
     int64_t r = r0 + qc;
     if (r > k_sel - 1) r = k_sel - 1;               // ragged last tile: duplicate a valid row, never stored
-    const int64_t qrow = q_is_compact ? r : (int64_t)idx_sel[r];
+    int64_t qrow = r;
+    if (!q_is_compact) {                            // an index outside [0, N) reads a valid row instead
+        const int32_t ix = idx_sel[r];
+        qrow = ix < 0 ? 0 : (ix > N - 1 ? N - 1 : (int64_t)ix);
+    }
     const __bf16 *qp = q + qrow * q_stride_n + (int64_t)head * q_stride_h + 8 * hf;
     bf16x8 qf[D / 16];
 #pragma unroll
@@ -466,6 +470,7 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
     // compact output row rr, or straight into the cached buffer's row of that token
     const int64_t orow = o_scatter ? (int64_t)idx_sel[rr] : rr;
     __bf16 *op = o_sel + orow * o_stride_n + (int64_t)head * D;
+    if (!o_scatter || (uint64_t)orow < (uint64_t)N)     // a row index outside the cached buffer writes nothing
 #pragma unroll
     for (int b = 0; b < 4; ++b)
 #pragma unroll
@@ -484,8 +489,9 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
 // O = sum_s w_s O_s / sum_s w_s l_s.  Workgroup (x, y) handles rows 8*y .. 8*y+7 of split item x; a
 // thread handles one row and four head-dim elements.
 __global__ __launch_bounds__(256) void merge_partials_kernel(const float *__restrict__ partial, AttnSchedule sch,
-                                                             int32_t H, int64_t k_sel, const int32_t *__restrict__ idx_sel,
-                                                             __bf16 *__restrict__ o_sel, int64_t o_stride_n, int o_scatter,
+                                                             int32_t H, int64_t k_sel, int64_t n_rows,
+                                                             const int32_t *__restrict__ idx_sel, __bf16 *__restrict__ o_sel,
+                                                             int64_t o_stride_n, int o_scatter,
                                                              float *__restrict__ lse_sel)
 {
     const int64_t left = sch.items_per_xcd - sch.full_items;
@@ -519,7 +525,8 @@ __global__ __launch_bounds__(256) void merge_partials_kernel(const float *__rest
         o4[0] = pack_bf16(acc.x * inv, acc.y * inv);
         o4[1] = pack_bf16(acc.z * inv, acc.w * inv);
         const int64_t orow = o_scatter ? (int64_t)idx_sel[rr] : rr;
-        *reinterpret_cast<uint2v *>(o_sel + orow * o_stride_n + (int64_t)head * D + d4) = o4;
+        if (!o_scatter || (uint64_t)orow < (uint64_t)n_rows)
+            *reinterpret_cast<uint2v *>(o_sel + orow * o_stride_n + (int64_t)head * D + d4) = o4;
         if (lse_sel && d4 == 0) lse_sel[rr * H + head] = (m_star + log2f(l)) * 0.69314718055994530942f;
     }
 }
@@ -594,7 +601,7 @@ int launch_attn_bf16_d128(const void *q, const void *k, const void *v, int64_t N
     kernel_timer_end(stream);
     if (left > 0)
         hipLaunchKernelGGL(merge_partials_kernel, dim3((unsigned)(left * kNumXcd), kBq / 8), dim3(256), 0, stream, partial, sch,
-                           H, k_sel, idx_sel, (__bf16 *)o_sel, o_stride_n, o_scatter, lse_sel);
+                           H, k_sel, N, idx_sel, (__bf16 *)o_sel, o_stride_n, o_scatter, lse_sel);
     return check_launch("astraea_sparse_attn_fwd(bf16)");
 }
 

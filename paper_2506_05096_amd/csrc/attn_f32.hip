@@ -50,7 +50,11 @@ __global__ __launch_bounds__(kWaves *kWave) void attn_f32_kernel(
     // Q operand: lane holds query column qc, head-dim elements 2s + hf
     int64_t r = r0 + qc;
     if (r > k_sel - 1) r = k_sel - 1;                    // ragged last tile: duplicate a valid row, never stored
-    const int64_t qrow = q_is_compact ? r : (int64_t)idx_sel[r];
+    int64_t qrow = r;
+    if (!q_is_compact) {                                 // an index outside [0, N) reads a valid row instead
+        const int32_t ix = idx_sel[r];
+        qrow = ix < 0 ? 0 : (ix > N - 1 ? N - 1 : (int64_t)ix);
+    }
     const float *qp = q + qrow * q_stride_n + (int64_t)head * q_stride_h;
     float qreg[D / 2];
 #pragma unroll
@@ -137,6 +141,7 @@ __global__ __launch_bounds__(kWaves *kWave) void attn_f32_kernel(
     // compact output row rr, or straight into the cached buffer's row of that token
     const int64_t orow = o_scatter ? (int64_t)idx_sel[rr] : rr;
     float *op = o_sel + orow * o_stride_n + (int64_t)head * D;
+    if (!o_scatter || (uint64_t)orow < (uint64_t)N)      // a row index outside the cached buffer writes nothing
 #pragma unroll
     for (int b = 0; b < DB; ++b)
 #pragma unroll

@@ -31,15 +31,15 @@ int launch_select_topk(const float *score, int64_t N, int64_t k, int32_t *idx_se
                        uint8_t *sel_mask, int32_t *skip_count, void *workspace, hipStream_t stream);
 
 int launch_move_rows(void *dst, const void *src, int64_t row_bytes, int64_t dst_stride_bytes,
-                     int64_t src_stride_bytes, const int32_t *idx, int64_t k_sel, bool index_dst, bool index_src,
-                     hipStream_t stream);
+                     int64_t src_stride_bytes, const int32_t *idx, int64_t k_sel, int64_t n_rows, bool index_dst,
+                     bool index_src, hipStream_t stream);
 
 int launch_lse_weight_update(const float *lse_sel, int32_t H, int64_t N, const int32_t *idx_sel, int64_t k_sel,
                              float *lse_weight, hipStream_t stream);
 
 int launch_linear_bf16(const void *x, const void *w, const void *bias, void *y, const int32_t *idx_sel, int64_t k_sel,
-                       int32_t c_in, int32_t c_out, int64_t ldx, int64_t ldy, int x_indexed, int y_indexed, int act,
-                       hipStream_t stream);
+                       int64_t n_rows, int32_t c_in, int32_t c_out, int64_t ldx, int64_t ldy, int x_indexed,
+                       int y_indexed, int act, hipStream_t stream);
 
 size_t attn_bf16_workspace_bytes(int64_t N, int32_t H);
 int launch_attn_bf16_d128(const void *q, const void *k, const void *v, int64_t N, int32_t H, int64_t q_stride_n,

@@ -53,6 +53,10 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b)
     floatx2 f = {a, b};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));   // v_cvt_pk_bf16_f32, RNE
 }
+__device__ __forceinline__ int32_t clamp_row(int32_t ix, int32_t n_rows)
+{
+    return ix < 0 ? 0 : (ix > n_rows - 1 ? n_rows - 1 : ix);
+}
 __device__ __forceinline__ bf16x8 lds_read_b128(uint32_t addr)
 {
     return *reinterpret_cast<const bf16x8 __attribute__((address_space(3))) *>((uintptr_t)addr);
@@ -92,6 +96,7 @@ struct LinearArgs {
     const int32_t *idx_sel;    // or null when neither side is indexed
     int64_t ldx, ldy;          // row strides in elements
     int32_t k_sel, c_in, c_out;
+    int32_t n_rows;            // rows of the indexed buffer(s): indices outside [0, n_rows) read a valid row, write none
     int32_t x_indexed, y_indexed, act;
     int32_t m_tiles, n_tiles, sb_n;   // tile counts and 4-wide super-block count along the features
 };
@@ -141,7 +146,7 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void linear_bf16_kernel(LinearArg
         woff[t] = (uint32_t)n * (uint32_t)a.c_in * 2u + (uint32_t)lchunk * 16u;
         int m = m0 + r;
         if (m > a.k_sel - 1) m = a.k_sel - 1;
-        const int64_t row = a.x_indexed ? (int64_t)a.idx_sel[m] : (int64_t)m;
+        const int64_t row = a.x_indexed ? (int64_t)clamp_row(a.idx_sel[m], a.n_rows) : (int64_t)m;
         xoff[t] = (uint32_t)(row * a.ldx * 2) + (uint32_t)lchunk * 16u;
     }
     // all index loads must have landed before the loop: a load still pending at the loop header would
@@ -163,7 +168,7 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void linear_bf16_kernel(LinearArg
         pf_w = (uint32_t)n * (uint32_t)a.c_in * 2u;
         int m = m0 + r;
         if (m > a.k_sel - 1) m = a.k_sel - 1;
-        const int64_t row = a.x_indexed ? (int64_t)a.idx_sel[m] : (int64_t)m;
+        const int64_t row = a.x_indexed ? (int64_t)clamp_row(a.idx_sel[m], a.n_rows) : (int64_t)m;
         pf_x = (uint32_t)(row * a.ldx * 2);
     }
     asm volatile("" ::"v"(pf_x), "v"(pf_w));
@@ -335,7 +340,11 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void linear_bf16_kernel(LinearArg
         for (int it = 0; it < 16; ++it) {
             int m = m0 + wm * 32 * kTb + 64 * jh + 4 * it + o_row;
             if (m > a.k_sel - 1) m = a.k_sel - 1;
-            orow[it] = a.y_indexed ? (int64_t)a.idx_sel[m] : (int64_t)m;
+            orow[it] = m;
+            if (a.y_indexed) {
+                const int32_t ix = a.idx_sel[m];
+                orow[it] = (uint32_t)ix < (uint32_t)a.n_rows ? (int64_t)ix : -1;     // -1: not stored
+            }
         }
 #pragma unroll
         for (int it = 0; it < 16; ++it) {
@@ -344,7 +353,7 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void linear_bf16_kernel(LinearArg
             const int n = n0 + wn * 128 + 8 * o_chunk;           // c_out is a multiple of 8: a chunk is all in or all out
             const uint4v val = *reinterpret_cast<const uint4v __attribute__((address_space(3))) *>(
                 (uintptr_t)(ebase + tl * kPitch + o_chunk * 16));
-            if (m < a.k_sel && n < a.c_out) *reinterpret_cast<uint4v *>(a.y + orow[it] * a.ldy + n) = val;
+            if (m < a.k_sel && n < a.c_out && orow[it] >= 0) *reinterpret_cast<uint4v *>(a.y + orow[it] * a.ldy + n) = val;
         }
         __builtin_amdgcn_s_waitcnt(0xc07f);                      // reads done before the second half overwrites
     }
@@ -353,7 +362,7 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void linear_bf16_kernel(LinearArg
 }  // namespace
 
 int launch_linear_bf16(const void *x, const void *w, const void *bias, void *y, const int32_t *idx_sel, int64_t k_sel,
-                       int32_t c_in, int32_t c_out, int64_t ldx, int64_t ldy, int x_indexed, int y_indexed, int act,
+                       int64_t n_rows, int32_t c_in, int32_t c_out, int64_t ldx, int64_t ldy, int x_indexed, int y_indexed, int act,
                        hipStream_t stream)
 {
     if (k_sel == 0) return ASTRAEA_OK;
@@ -366,6 +375,7 @@ int launch_linear_bf16(const void *x, const void *w, const void *bias, void *y, 
     a.ldx = ldx;
     a.ldy = ldy;
     a.k_sel = (int32_t)k_sel;
+    a.n_rows = (int32_t)n_rows;
     a.c_in = c_in;
     a.c_out = c_out;
     a.x_indexed = x_indexed;

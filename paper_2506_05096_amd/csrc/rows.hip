@@ -17,12 +17,13 @@ constexpr int kRowsPerBlock = 4;      // one wave per row
 template <typename V>
 __global__ __launch_bounds__(kRowsPerBlock *kWave) void move_rows_kernel(
     char *__restrict__ dst, const char *__restrict__ src, int64_t row_bytes, int64_t dst_stride, int64_t src_stride,
-    const int32_t *__restrict__ idx, int64_t k_sel, int index_dst, int index_src)
+    const int32_t *__restrict__ idx, int64_t k_sel, int64_t n_rows, int index_dst, int index_src)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t r = (int64_t)blockIdx.x * kRowsPerBlock + threadIdx.x / kWave;
     if (r >= k_sel) return;
     const int64_t tok = idx[r];
+    if ((uint64_t)tok >= (uint64_t)n_rows) return;      // an index outside the buffer moves nothing
     const V *s = reinterpret_cast<const V *>(src + (index_src ? tok : r) * src_stride);
     V *d = reinterpret_cast<V *>(dst + (index_dst ? tok : r) * dst_stride);
     const int64_t nvec = row_bytes / (int64_t)sizeof(V);
@@ -47,14 +48,15 @@ __global__ __launch_bounds__(kRowsPerBlock *kWave) void move_rows_kernel(
 
 // lse_weight[idx[r]] = mean over heads of exp(lse[r, h] - ln N); one thread per selected token.
 __global__ __launch_bounds__(256) void lse_weight_kernel(const float *__restrict__ lse_sel, int32_t H, float log_n,
-                                                         const int32_t *__restrict__ idx, int64_t k_sel,
+                                                         const int32_t *__restrict__ idx, int64_t k_sel, int64_t n_rows,
                                                          float *__restrict__ lse_weight)
 {
     const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (r >= k_sel) return;
     float acc = 0.0f;
     for (int h = 0; h < H; ++h) acc += expf(lse_sel[r * H + h] - log_n);
-    lse_weight[idx[r]] = acc / (float)H;
+    const int64_t tok = idx[r];
+    if ((uint64_t)tok < (uint64_t)n_rows) lse_weight[tok] = acc / (float)H;
 }
 
 }  // namespace
@@ -64,13 +66,13 @@ int launch_lse_weight_update(const float *lse_sel, int32_t H, int64_t N, const i
 {
     if (k_sel == 0) return ASTRAEA_OK;
     hipLaunchKernelGGL(lse_weight_kernel, dim3((unsigned)((k_sel + 255) / 256)), dim3(256), 0, stream, lse_sel, H,
-                       logf((float)N), idx_sel, k_sel, lse_weight);
+                       logf((float)N), idx_sel, k_sel, N, lse_weight);
     return check_launch("astraea_lse_weight_update");
 }
 
 int launch_move_rows(void *dst, const void *src, int64_t row_bytes, int64_t dst_stride_bytes,
-                     int64_t src_stride_bytes, const int32_t *idx, int64_t k_sel, bool index_dst, bool index_src,
-                     hipStream_t stream)
+                     int64_t src_stride_bytes, const int32_t *idx, int64_t k_sel, int64_t n_rows, bool index_dst,
+                     bool index_src, hipStream_t stream)
 {
     if (k_sel == 0 || row_bytes == 0) return ASTRAEA_OK;
     dim3 grid((unsigned)((k_sel + kRowsPerBlock - 1) / kRowsPerBlock)), block(kRowsPerBlock * kWave);
@@ -78,13 +80,13 @@ int launch_move_rows(void *dst, const void *src, int64_t row_bytes, int64_t dst_
                           (uintptr_t)src_stride_bytes;
     if (all % 16 == 0)
         hipLaunchKernelGGL(move_rows_kernel<uint4v>, grid, block, 0, stream, (char *)dst, (const char *)src, row_bytes,
-                           dst_stride_bytes, src_stride_bytes, idx, k_sel, (int)index_dst, (int)index_src);
+                           dst_stride_bytes, src_stride_bytes, idx, k_sel, n_rows, (int)index_dst, (int)index_src);
     else if (all % 4 == 0)
         hipLaunchKernelGGL(move_rows_kernel<uint32_t>, grid, block, 0, stream, (char *)dst, (const char *)src,
-                           row_bytes, dst_stride_bytes, src_stride_bytes, idx, k_sel, (int)index_dst, (int)index_src);
+                           row_bytes, dst_stride_bytes, src_stride_bytes, idx, k_sel, n_rows, (int)index_dst, (int)index_src);
     else
         hipLaunchKernelGGL(move_rows_kernel<uint16_t>, grid, block, 0, stream, (char *)dst, (const char *)src,
-                           row_bytes, dst_stride_bytes, src_stride_bytes, idx, k_sel, (int)index_dst, (int)index_src);
+                           row_bytes, dst_stride_bytes, src_stride_bytes, idx, k_sel, n_rows, (int)index_dst, (int)index_src);
     return check_launch("astraea row move");
 }
 
