@@ -74,6 +74,18 @@ def _dtype_code(a: np.ndarray) -> int:
     raise TypeError(f"oracle arrays must be float32 or uint16 (bf16 bits), got {a.dtype}")
 
 
+def _rows(a: np.ndarray, *others: np.ndarray):
+    """2-D arrays whose rows are contiguous but may lie further apart than their length (a column slice of a
+    wider array): returned as they are with their common row stride in elements; anything else is copied."""
+    arrs = (a,) + others
+    es = a.itemsize
+    ok = all(x.ndim == 2 and x.strides[1] == es and x.strides[0] % es == 0 and x.strides[0] >= x.shape[1] * es
+             and x.strides[0] == a.strides[0] for x in arrs)
+    if not ok:
+        arrs = tuple(np.ascontiguousarray(x) for x in arrs)
+    return arrs + (arrs[0].strides[0] // es,)
+
+
 def _check(rc: int, what: str):
     if rc != 0:
         raise RuntimeError(f"{what} failed with status {rc}")
@@ -82,7 +94,7 @@ def _check(rc: int, what: str):
 def score(x_cur: np.ndarray, x_prev: np.ndarray, mode: int = DELTA_L2, lse_weight=None, skip_count=None,
           penalty_table=None, w_alpha: float = 1.0, w_beta: float = 0.0) -> np.ndarray:
     assert x_cur.ndim == 2 and x_cur.shape == x_prev.shape and x_cur.dtype == x_prev.dtype
-    x_cur, x_prev = np.ascontiguousarray(x_cur), np.ascontiguousarray(x_prev)
+    x_cur, x_prev, stride = _rows(x_cur, x_prev)
     n, c = x_cur.shape
     out = np.empty(n, dtype=np.float32)
     if lse_weight is not None:
@@ -91,20 +103,20 @@ def score(x_cur: np.ndarray, x_prev: np.ndarray, mode: int = DELTA_L2, lse_weigh
         skip_count = np.ascontiguousarray(skip_count, dtype=np.int32)
         penalty_table = np.ascontiguousarray(penalty_table, dtype=np.float32)
     tl = 0 if penalty_table is None else int(penalty_table.shape[0])
-    _check(lib().oracle_score(_ptr(x_cur), _ptr(x_prev), _dtype_code(x_cur), n, c, c, mode, _ptr(lse_weight),
+    _check(lib().oracle_score(_ptr(x_cur), _ptr(x_prev), _dtype_code(x_cur), n, c, stride, mode, _ptr(lse_weight),
                               _ptr(skip_count), _ptr(penalty_table), tl, w_alpha, w_beta, _ptr(out)), "oracle_score")
     return out
 
 
 def score_f64(x_cur, x_prev, mode=DELTA_L2, lse_weight=None, skip_count=None, w_alpha=1.0, w_beta=0.0) -> np.ndarray:
-    x_cur, x_prev = np.ascontiguousarray(x_cur), np.ascontiguousarray(x_prev)
+    x_cur, x_prev, stride = _rows(x_cur, x_prev)
     n, c = x_cur.shape
     out = np.empty(n, dtype=np.float64)
     if lse_weight is not None:
         lse_weight = np.ascontiguousarray(lse_weight, dtype=np.float32)
     if skip_count is not None:
         skip_count = np.ascontiguousarray(skip_count, dtype=np.int32)
-    _check(lib().oracle_score_f64(_ptr(x_cur), _ptr(x_prev), _dtype_code(x_cur), n, c, c, mode, _ptr(lse_weight),
+    _check(lib().oracle_score_f64(_ptr(x_cur), _ptr(x_prev), _dtype_code(x_cur), n, c, stride, mode, _ptr(lse_weight),
                                   _ptr(skip_count), w_alpha, w_beta, _ptr(out)), "oracle_score_f64")
     return out
 
@@ -169,21 +181,23 @@ def round_to_dtype(x64: np.ndarray, dtype_code: int) -> np.ndarray:
 
 
 def scatter(cache: np.ndarray, src: np.ndarray, idx_sel, src_is_full: bool = False) -> None:
-    """In place: cache[idx[r]] = src[r] (or src[idx[r]] when src_is_full)."""
-    assert cache.flags.c_contiguous and cache.ndim == 2 and cache.dtype == src.dtype
-    src = np.ascontiguousarray(src)
+    """In place: cache[idx[r]] = src[r] (or src[idx[r]] when src_is_full).  cache and src may be column slices
+    of wider arrays."""
+    assert cache.ndim == 2 and cache.dtype == src.dtype and src.ndim == 2 and src.shape[1] == cache.shape[1]
+    (cache_v, cs), (src, ss) = _rows(cache), _rows(src)
+    assert cache_v is cache, "the cache is updated in place: its rows must be contiguous"
     idx = np.ascontiguousarray(idx_sel, dtype=np.int32)
     n, e = cache.shape
-    _check(lib().oracle_scatter(_ptr(cache), _ptr(src), _dtype_code(cache), n, e, e, e, _ptr(idx), idx.shape[0],
+    _check(lib().oracle_scatter(_ptr(cache), _ptr(src), _dtype_code(cache), n, e, cs, ss, _ptr(idx), idx.shape[0],
                                 1 if src_is_full else 0), "oracle_scatter")
 
 
 def gather(src: np.ndarray, idx_sel) -> np.ndarray:
-    src = np.ascontiguousarray(src)
+    src, ss = _rows(src)
     idx = np.ascontiguousarray(idx_sel, dtype=np.int32)
     n, e = src.shape
     dst = np.empty((idx.shape[0], e), dtype=src.dtype)
-    _check(lib().oracle_gather(_ptr(src), _ptr(dst), _dtype_code(src), n, e, e, e, _ptr(idx), idx.shape[0]),
+    _check(lib().oracle_gather(_ptr(src), _ptr(dst), _dtype_code(src), n, e, ss, e, _ptr(idx), idx.shape[0]),
            "oracle_gather")
     return dst
 

@@ -97,6 +97,18 @@ def repair(theta: Sequence[int], budget: int, rng: SplitMix64) -> List[int]:
     return out
 
 
+def parent_pair(k: int, rng: SplitMix64) -> Tuple[int, int]:
+    """Two parents drawn from the k candidates of the current population (Sec. 3.3 "Algorithm": a random pair).
+    Reading: uniform over ordered pairs of distinct candidates; with a single candidate it is its own partner."""
+    a = rng.below(k)
+    b = a
+    if k > 1:
+        b = rng.below(k - 1)
+        if b >= a:
+            b += 1
+    return a, b
+
+
 def search(T: int, budget: int, population: int, children: int, generations: int, p_start: float, p_final: float,
            seed: int, fitness: Callable[[Sequence[int]], float], max_attempts_factor: int = 64):
     """The search loop (supplementary algorithm; Sec. 3.3 "Algorithm").
@@ -127,12 +139,7 @@ def search(T: int, budget: int, population: int, children: int, generations: int
         attempts = 0
         while len(new) < children and attempts < max_attempts_factor * children:
             attempts += 1
-            a = rng.below(k)
-            b = a
-            if k > 1:
-                b = rng.below(k - 1)
-                if b >= a:
-                    b += 1
+            a, b = parent_pair(k, rng)
             if rng.below(2) == 0:
                 child = crossover_uniform(pop[a], pop[b], rng)
             else:

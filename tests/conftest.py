@@ -8,6 +8,10 @@ import pytest
 ROOT = Path(__file__).resolve().parents[1]
 if str(ROOT) not in sys.path:
     sys.path.insert(0, str(ROOT))
+# test_oracle_mutants.py runs the pins in a child process against a copy of the oracle with a planted mistake:
+# that copy's parent directory then goes in front of the repository
+if os.environ.get("ASTRAEA_TEST_ORACLE_ROOT"):
+    sys.path.insert(0, os.environ["ASTRAEA_TEST_ORACLE_ROOT"])
 
 
 def pytest_configure(config):

@@ -62,8 +62,42 @@ def test_crossover_takes_every_gene_from_a_parent_at_the_same_position():
     assert max(lengths) > T // 2                  # blocks of all sizes occur
     # genes are copied by position, not by value
     a, b = list(range(10)), list(range(100, 110))
-    c = ob.crossover_block(a, b, ob.SplitMix64(1))
-    assert all(c[i] in (a[i], b[i]) for i in range(10))
+    for seed in range(20):
+        for op in (ob.crossover_block, ob.crossover_uniform):
+            c = op(a, b, ob.SplitMix64(seed))
+            assert all(c[i] in (a[i], b[i]) for i in range(10))
+
+
+def test_block_crossover_range_has_uniform_ends():
+    """Both ends uniform on 0..T, the range [lo, hi) from the first parent: timestep i then comes from it with
+    probability 1 - ((i + 1) / (T + 1))^2 - ((T - i) / (T + 1))^2, the whole child with 2 / (T + 1)^2."""
+    T, draws = 6, 40000
+    p0, p1 = [0] * T, [1] * T
+    r = ob.SplitMix64(11)
+    from_p0 = np.zeros(T)
+    whole = 0
+    for _ in range(draws):
+        c = ob.crossover_block(p0, p1, r)
+        from_p0 += 1 - np.array(c)
+        whole += sum(c) == 0
+    want = np.array([1 - ((i + 1) / (T + 1)) ** 2 - ((T - i) / (T + 1)) ** 2 for i in range(T)])
+    assert np.all(np.abs(from_p0 / draws - want) < 4 * np.sqrt(want * (1 - want) / draws))
+    pw = 2 / (T + 1) ** 2
+    assert abs(whole / draws - pw) < 4 * np.sqrt(pw * (1 - pw) / draws)
+
+
+def test_parent_pairs_are_distinct_and_uniform():
+    k, draws = 4, 24000
+    r = ob.SplitMix64(21)
+    counts = np.zeros((k, k))
+    for _ in range(draws):
+        a, b = ob.parent_pair(k, r)
+        counts[a, b] += 1
+    assert np.all(np.diag(counts) == 0)
+    off = counts[~np.eye(k, dtype=bool)] / draws
+    p = 1 / (k * (k - 1))
+    assert np.all(np.abs(off - p) < 4 * np.sqrt(p * (1 - p) / draws))
+    assert ob.parent_pair(1, ob.SplitMix64(0)) == (0, 0)
 
 
 def test_mutation_probability_schedule():

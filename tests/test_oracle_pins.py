@@ -91,6 +91,23 @@ def test_score_row_indexing_not_transposed():
     assert np.array_equal(oracle.score(cur, prev), np.arange(1, N + 1, dtype=np.float32))
 
 
+def test_score_rows_further_apart_than_their_length():
+    """Feature rows taken as a column slice of wider arrays (different padding behind the two operands): the
+    padding is never read and each operand is indexed with the row stride."""
+    rng = np.random.default_rng(5)
+    n, c, pad = 9, 37, 6
+    big_cur = rng.standard_normal((n, c + pad)).astype(np.float32)
+    big_prev = rng.standard_normal((n, c + pad)).astype(np.float32)
+    cur, prev = big_cur[:, :c], big_prev[:, :c]
+    assert not cur.flags.c_contiguous
+    for mode in (oracle.DELTA_L2, oracle.DELTA_MEAN_ABS, oracle.DELTA_MEAN_SQ):
+        want = oracle.score(cur.copy(), prev.copy(), mode)
+        assert np.array_equal(oracle.score(cur, prev, mode), want)
+        assert np.array_equal(oracle.score_f64(cur, prev, mode), oracle.score_f64(cur.copy(), prev.copy(), mode))
+    ref = np.sqrt(((cur.astype(np.float64) - prev.astype(np.float64)) ** 2).sum(axis=1))
+    assert np.allclose(oracle.score(cur, prev), ref, rtol=1e-6)
+
+
 def test_score_bf16_bit_patterns_decode():
     # 0x3F80 = 1.0, 0x4000 = 2.0, 0xC040 = -3.0 in bfloat16
     cur = np.array([[0x3F80, 0x4000, 0xC040, 0x0000]], np.uint16)
@@ -364,6 +381,27 @@ def test_scatter_gather_properties(dt):
     assert np.array_equal(c[rest], cache0[rest]) and np.array_equal(c[idx], full[idx])
 
 
+def test_scatter_gather_with_padded_rows():
+    """Cache and sources whose rows lie further apart than their length: only the row_elems columns move, the
+    padding behind them keeps its bits, and every buffer is indexed with its own row stride."""
+    rng = np.random.default_rng(8)
+    n, e, k = 30, 6, 11
+    big = rng.integers(0, 60000, (n, e + 4)).astype(np.uint16)
+    big0 = big.copy()
+    idx = np.sort(rng.choice(n, k, replace=False)).astype(np.int32)
+    src_big = rng.integers(0, 60000, (k, e + 2)).astype(np.uint16)
+    oracle.scatter(big[:, :e], src_big[:, :e], idx)
+    assert np.array_equal(big[:, e:], big0[:, e:])
+    rest = np.setdiff1d(np.arange(n), idx)
+    assert np.array_equal(big[rest], big0[rest]) and np.array_equal(big[idx, :e], src_big[:, :e])
+    assert np.array_equal(oracle.gather(big[:, :e], idx), src_big[:, :e])
+    full_big = rng.integers(0, 60000, (n, e + 3)).astype(np.uint16)
+    big = big0.copy()
+    oracle.scatter(big[:, :e], full_big[:, :e], idx, src_is_full=True)
+    assert np.array_equal(big[idx, :e], full_big[idx, :e]) and np.array_equal(big[rest], big0[rest])
+    assert np.array_equal(big[:, e:], big0[:, e:])
+
+
 def test_round_to_bf16_is_single_rne():
     x = np.array([1.0, 1.0 + 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -40, 1.0 + 3 * 2.0 ** -8, -2.5, 0.0,
                   1.0 + 2.0 ** -8 - 2.0 ** -40, 3.0e38 * 10], np.float64)
@@ -377,6 +415,13 @@ def test_round_to_bf16_is_single_rne():
     ref = torch.tensor(x[plain], dtype=torch.float64).to(torch.bfloat16).double().numpy()
     assert np.array_equal(got[plain], ref)
     assert np.array_equal(oracle.round_to_dtype(x[:7], oracle.F32), x[:7].astype(np.float32))
+    # off the midpoints: up past it, down before it
+    y = np.array([1.0 + 2.0 ** -8 + 2.0 ** -12, 1.0 + 2.0 ** -9, -(1.0 + 2.0 ** -8 + 2.0 ** -12), 1.0 + 2.0 ** -7 - 2.0 ** -20])
+    assert bf16_bits_to_f64(oracle.round_to_dtype(y, oracle.BF16)).tolist() == [1.0 + 2.0 ** -7, 1.0, -(1.0 + 2.0 ** -7), 1.0 + 2.0 ** -7]
+    # the library's cast on values that are exact in fp32 (its route through fp32 then rounds only once)
+    z = torch.randn(4096, generator=torch.Generator().manual_seed(3)) * 37.0
+    got = bf16_bits_to_f64(oracle.round_to_dtype(z.double().numpy(), oracle.BF16))
+    assert np.array_equal(got, z.to(torch.bfloat16).double().numpy())
 
 
 # ---------------------------------------------------------- flop accounting --
