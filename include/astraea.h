@@ -265,6 +265,19 @@ int64_t astraea_budget_to_k(int64_t N, int32_t budget_percent);
 double astraea_attn_flops(int64_t N, int64_t k_sel, int32_t H, int32_t D);
 
 /*
+ * How the bf16 attention would spread k_sel selected queries of H heads over the chip (the
+ * budget-aware launch: time proportional to the selected-token count, paper Sec. 3.2 "linear
+ * speedup").  Host only, nothing is enqueued; for inspection and tests.  A work item is one head
+ * times one tile of 256 selected queries, head-major; XCD x (of 8) owns items
+ * [x*items_per_xcd, (x+1)*items_per_xcd).  The first full_items of each XCD sweep all key tiles
+ * (64 keys each); every later item is cut into `splits` consecutive key ranges of tiles_per_split
+ * tiles, each run by its own workgroup, whose partial results a second kernel combines.
+ * plan_out (host, 8 entries): q_tiles, items_per_xcd, full_items, splits, tiles_per_split,
+ * workgroups launched, key tiles, partial-result slots the workspace holds.
+ */
+int astraea_attn_plan(int64_t N, int32_t H, int64_t k_sel, int64_t plan_out[8]);
+
+/*
  * Measurement aids for the benchmark; neither is a step of the method.
  *
  * astraea_probe_mfma_bf16 runs a register-resident loop of v_mfma_f32_32x32x16_bf16

@@ -252,6 +252,15 @@ double astraea_attn_flops(int64_t N, int64_t k_sel, int32_t H, int32_t D)
     return 4.0 * (double)k_sel * (double)N * (double)D * (double)H;
 }
 
+int astraea_attn_plan(int64_t N, int32_t H, int64_t k_sel, int64_t plan_out[8])
+{
+    if (!plan_out) return fail(ASTRAEA_ERR_INVALID, "astraea_attn_plan: NULL output");
+    if (N <= 0 || N > kMaxTokens || H <= 0 || H > 65535 || k_sel <= 0 || k_sel > kMaxTokens)
+        return fail(ASTRAEA_ERR_INVALID, "astraea_attn_plan: N=%lld, H=%d, k_sel=%lld out of range", (long long)N, (int)H,
+                    (long long)k_sel);
+    return attn_bf16_plan(N, H, k_sel, plan_out);
+}
+
 const char *astraea_status_string(int status)
 {
     switch (status) {

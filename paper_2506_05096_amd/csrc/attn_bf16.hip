@@ -533,32 +533,12 @@ __global__ __launch_bounds__(256) void merge_partials_kernel(const float *__rest
 
 }  // namespace
 
-// Workspace of the bf16 path: the V^T tiles written by the pre-pass, then the partial results of the
-// split items (at most kMaxSharesPerXcd shares per XCD).
-static size_t vt_bytes(int64_t N, int32_t H)
+// The budget-aware split for k_sel selected queries of H heads over N keys; `slots` = workgroups per XCD.
+// False when the grid would not fit.
+static bool plan_attn(int64_t N, int32_t H, int64_t k_sel, AttnSchedule &sch, int64_t &slots)
 {
-    const int64_t ntiles = (N + kBk - 1) / kBk;
-    return (size_t)ntiles * (size_t)H * kTileBytes;
-}
-size_t attn_bf16_workspace_bytes(int64_t N, int32_t H)
-{
-    if (N <= 0 || H <= 0) return 0;
-    return vt_bytes(N, H) + (size_t)kNumXcd * kMaxSharesPerXcd * kPartialFloats * sizeof(float);
-}
-
-int launch_attn_bf16_d128(const void *q, const void *k, const void *v, int64_t N, int32_t H, int64_t q_stride_n,
-                          int64_t q_stride_h, int64_t kv_stride_n, int64_t kv_stride_h, const int32_t *idx_sel,
-                          int64_t k_sel, int q_is_compact, float scale, void *o_sel, int64_t o_stride_n, int o_scatter,
-                          float *lse_sel, void *workspace,
-                          hipStream_t stream)
-{
-    if (k_sel == 0) return ASTRAEA_OK;
-    // a tile's lane offsets are 32-bit: 64 rows must span less than 4 GiB
-    if (kv_stride_n * 2 * kBk >= (int64_t)1 << 32)
-        return fail(ASTRAEA_ERR_UNSUPPORTED, "astraea_sparse_attn_fwd: K/V token stride too large");
     const int64_t ntiles = (N + kBk - 1) / kBk;
     constexpr int kCuPerXcd = 32;
-    AttnSchedule sch;
     sch.q_tiles = (int32_t)((k_sel + kBq - 1) / kBq);
     const int64_t total = (int64_t)sch.q_tiles * H;
     sch.items_per_xcd = (total + kNumXcd - 1) / kNumXcd;
@@ -585,9 +565,55 @@ int launch_attn_bf16_d128(const void *q, const void *k, const void *v, int64_t N
     sch.full_items = sch.items_per_xcd - left;
     sch.splits = (int32_t)splits;
     sch.tiles_per_split = (ntiles + splits - 1) / splits;
-    const int64_t slots = sch.full_items + left * splits;
-    if (slots * kNumXcd > 2147483647LL || ntiles > 2147483647LL)
+    slots = sch.full_items + left * splits;
+    return slots * kNumXcd <= 2147483647LL && ntiles <= 2147483647LL;
+}
+
+int attn_bf16_plan(int64_t N, int32_t H, int64_t k_sel, int64_t plan[8])
+{
+    AttnSchedule sch;
+    int64_t slots = 0;
+    if (!plan_attn(N, H, k_sel, sch, slots)) return fail(ASTRAEA_ERR_INVALID, "astraea_attn_plan: grid too large");
+    plan[0] = sch.q_tiles;
+    plan[1] = sch.items_per_xcd;
+    plan[2] = sch.full_items;
+    plan[3] = sch.splits;
+    plan[4] = sch.tiles_per_split;
+    plan[5] = slots * kNumXcd;
+    plan[6] = (N + kBk - 1) / kBk;
+    plan[7] = (int64_t)kNumXcd * kMaxSharesPerXcd;
+    return ASTRAEA_OK;
+}
+
+// Workspace of the bf16 path: the V^T tiles written by the pre-pass, then the partial results of the
+// split items (at most kMaxSharesPerXcd shares per XCD).
+static size_t vt_bytes(int64_t N, int32_t H)
+{
+    const int64_t ntiles = (N + kBk - 1) / kBk;
+    return (size_t)ntiles * (size_t)H * kTileBytes;
+}
+size_t attn_bf16_workspace_bytes(int64_t N, int32_t H)
+{
+    if (N <= 0 || H <= 0) return 0;
+    return vt_bytes(N, H) + (size_t)kNumXcd * kMaxSharesPerXcd * kPartialFloats * sizeof(float);
+}
+
+int launch_attn_bf16_d128(const void *q, const void *k, const void *v, int64_t N, int32_t H, int64_t q_stride_n,
+                          int64_t q_stride_h, int64_t kv_stride_n, int64_t kv_stride_h, const int32_t *idx_sel,
+                          int64_t k_sel, int q_is_compact, float scale, void *o_sel, int64_t o_stride_n, int o_scatter,
+                          float *lse_sel, void *workspace,
+                          hipStream_t stream)
+{
+    if (k_sel == 0) return ASTRAEA_OK;
+    // a tile's lane offsets are 32-bit: 64 rows must span less than 4 GiB
+    if (kv_stride_n * 2 * kBk >= (int64_t)1 << 32)
+        return fail(ASTRAEA_ERR_UNSUPPORTED, "astraea_sparse_attn_fwd: K/V token stride too large");
+    const int64_t ntiles = (N + kBk - 1) / kBk;
+    AttnSchedule sch;
+    int64_t slots = 0;
+    if (!plan_attn(N, H, k_sel, sch, slots))
         return fail(ASTRAEA_ERR_INVALID, "astraea_sparse_attn_fwd: grid too large");
+    const int64_t left = sch.items_per_xcd - sch.full_items;
     char *vt = (char *)workspace;
     float *partial = (float *)(vt + vt_bytes(N, H));
     hipLaunchKernelGGL(transpose_v_kernel, dim3((unsigned)ntiles, (unsigned)H), dim3(256), 0, stream,

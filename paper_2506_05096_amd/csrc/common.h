@@ -42,6 +42,7 @@ int launch_linear_bf16(const void *x, const void *w, const void *bias, void *y, 
                        int y_indexed, int act, hipStream_t stream);
 
 size_t attn_bf16_workspace_bytes(int64_t N, int32_t H);
+int attn_bf16_plan(int64_t N, int32_t H, int64_t k_sel, int64_t plan[8]);
 int launch_attn_bf16_d128(const void *q, const void *k, const void *v, int64_t N, int32_t H, int64_t q_stride_n,
                           int64_t q_stride_h, int64_t kv_stride_n, int64_t kv_stride_h, const int32_t *idx_sel,
                           int64_t k_sel, int q_is_compact, float scale, void *o_sel, int64_t o_stride_n, int o_scatter,

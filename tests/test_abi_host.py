@@ -208,3 +208,79 @@ def test_synthetic_workloads_have_the_configured_shapes():
     assert t["q"].shape == (128, 24, 128) and t["x_cur"].shape == (128, 3072) and t["out_cache"].shape == (128, 3072)
     t2 = synth.make_layer_inputs(w["cfg2"], seed=0, N=128)
     assert all((t[k].view(-1) == t2[k].view(-1)).all() for k in t)
+
+
+# ------------------------------------------------------ budget-aware launch plan --
+
+def _covered(plan, H):
+    """Walks every workgroup of the plan the way the header describes it and returns, per work item, the list of
+    key-tile ranges its workgroups take, plus the partial-result slots used."""
+    q_tiles, ipx, full, splits, tps, wgs, key_tiles, _ = (plan[n] for n in (
+        "q_tiles", "items_per_xcd", "full_items", "splits", "tiles_per_split", "workgroups", "key_tiles",
+        "partial_slots"))
+    total = q_tiles * H
+    ranges, slots = {}, []
+    for wg in range(wgs):
+        xcd, slot = wg % 8, wg // 8
+        if slot < full:
+            item, lo, hi, ps = xcd * ipx + slot, 0, key_tiles, None
+        else:
+            p = slot - full
+            li, sp = p // splits, p % splits
+            item = xcd * ipx + full + li
+            lo, hi = sp * tps, min((sp + 1) * tps, key_tiles)
+            ps = (xcd * (ipx - full) + li) * splits + sp
+        if item >= (xcd + 1) * ipx or item >= total:
+            continue
+        ranges.setdefault(item, []).append((lo, hi))
+        if ps is not None:
+            slots.append(ps)
+    return ranges, slots
+
+
+def test_attention_plan_covers_every_item_and_key_tile_once():
+    import random
+    rnd = random.Random(0)
+    cases = [(118800, 24, k) for k in (1, 255, 256, 257, 11880, 35640, 118800)]
+    cases += [(17550, 24, 7020), (16384, 24, 4096), (1, 1, 1), (63, 2, 63), (77, 3, 1000), (64, 65535, 1)]
+    cases += [(rnd.randint(1, 5000), rnd.randint(1, 40), rnd.randint(1, 60000)) for _ in range(300)]
+    for N, H, k in cases:
+        plan = ab.astraea_attn_plan(N, H, k)
+        assert plan["q_tiles"] == -(-k // 256) and plan["key_tiles"] == -(-N // 64), (N, H, k)
+        ranges, slots = _covered(plan, H)
+        total = plan["q_tiles"] * H
+        assert sorted(ranges) == list(range(total)), (N, H, k)                 # every (head, query tile) is taken
+        for item, rs in ranges.items():
+            rs.sort()
+            assert rs[0][0] == 0 and rs[-1][1] == plan["key_tiles"], (N, H, k, item)
+            assert all(a[1] == b[0] for a, b in zip(rs, rs[1:])), (N, H, k, item)   # ranges abut: each tile once
+            assert all(lo < hi for lo, hi in rs), (N, H, k, item)                   # no empty share
+            assert len(rs) in (1, plan["splits"])
+        assert len(set(slots)) == len(slots) and all(0 <= s < plan["partial_slots"] for s in slots), (N, H, k)
+        # the tail of each XCD is cut only when that shortens it, and never into more than 64 shares
+        left = plan["items_per_xcd"] - plan["full_items"]
+        assert 0 <= left < 32 and left * plan["splits"] <= 64 and 1 <= plan["splits"] <= 8
+        assert plan["full_items"] % 32 == 0 or left == 0
+
+
+def test_attention_plan_work_follows_the_budget():
+    """Rounds of 32 workgroups per XCD, each weighted by the share of the keys it sweeps: the plan's cost stays
+    within 10 % of proportional to k_sel from the 10 % budget up, at the headline shape."""
+    N, H = 118800, 24
+    cost = {}
+    for pct in range(10, 101, 10):
+        p = ab.astraea_attn_plan(N, H, N * pct // 100)
+        left = p["items_per_xcd"] - p["full_items"]
+        tail = -(-left * p["splits"] // 32) * p["tiles_per_split"] / p["key_tiles"]
+        cost[pct] = p["full_items"] / 32 + tail
+    unit = cost[100] / 100
+    assert all(abs(cost[pct] / (unit * pct) - 1) < 0.10 for pct in cost), cost
+
+
+def test_attention_plan_rejects_bad_arguments(L):
+    out = (C.c_int64 * 8)()
+    assert L.astraea_attn_plan(0, 1, 1, out) == ab.ERR_INVALID
+    assert L.astraea_attn_plan(10, 0, 1, out) == ab.ERR_INVALID
+    assert L.astraea_attn_plan(10, 1, 0, out) == ab.ERR_INVALID
+    assert L.astraea_attn_plan(10, 1, 1, None) == ab.ERR_INVALID
+    assert L.astraea_attn_plan(10, 1, 1, out) == ab.OK
