@@ -106,7 +106,8 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const __bf16 *__restri
         const int row = (tid >> 4) + 16 * i, c16 = tid & 15;
         const int64_t key = T * kBk + row;
         uint4v val = {0u, 0u, 0u, 0u};
-        if (key < N) val = *reinterpret_cast<const uint4v *>(vb + key * kv_stride_n + c16 * 8);
+        // V is read once here: streaming hint, the lines are not kept in L2
+        if (key < N) val = __builtin_nontemporal_load(reinterpret_cast<const uint4v *>(vb + key * kv_stride_n + c16 * 8));
         uint32_t *dst = reinterpret_cast<uint32_t *>(&tile[row][c16 * 8]);
         dst[0] = val[0];
         dst[1] = val[1];

