@@ -265,6 +265,17 @@ int64_t astraea_budget_to_k(int64_t N, int32_t budget_percent);
 double astraea_attn_flops(int64_t N, int64_t k_sel, int32_t H, int32_t D);
 
 /*
+ * Debugging aid for callers that build idx_sel themselves: counts, on the device, the entries that
+ * break the contract of the calls above.  counts_out (device, 2 x int32, overwritten):
+ *   [0] entries outside [0, N);
+ *   [1] positions r >= 1 with idx_sel[r] <= idx_sel[r-1], i.e. where the list is not strictly
+ *       ascending, the form astraea_select_topk emits (a list with [1] == 0 has no duplicates;
+ *       a list with [1] > 0 may still be duplicate-free, only not in that form).
+ * Asynchronous on `stream` like every other call; the caller reads the counts when it chooses.
+ */
+int astraea_check_indices(const int32_t *idx_sel, int64_t k_sel, int64_t N, int32_t *counts_out, void *stream);
+
+/*
  * How the bf16 attention would spread k_sel selected queries of H heads over the chip (the
  * budget-aware launch: time proportional to the selected-token count, paper Sec. 3.2 "linear
  * speedup").  Host only, nothing is enqueued; for inspection and tests.  A work item is one head

@@ -28,7 +28,7 @@ EXPORTS = (
     "astraea_score", "astraea_select_topk", "astraea_sparse_attn_fwd", "astraea_sparse_attn_update_fwd",
     "astraea_scatter_update", "astraea_gather_rows", "astraea_sparse_linear", "astraea_workspace_bytes", "astraea_budget_to_k", "astraea_attn_flops",
     "astraea_probe_mfma_bf16", "astraea_probe_copy", "astraea_probe_kernel_timer", "astraea_probe_kernel_count",
-    "astraea_probe_kernel_ms", "astraea_lse_weight_update", "astraea_attn_plan",
+    "astraea_probe_kernel_ms", "astraea_lse_weight_update", "astraea_attn_plan", "astraea_check_indices",
     "astraea_budget_search", "astraea_search_crossover", "astraea_search_mutate", "astraea_search_repair",
     "astraea_status_string", "astraea_last_error",
 )
@@ -86,6 +86,8 @@ def lib() -> C.CDLL:
         L.astraea_lse_weight_update.restype = C.c_int
         L.astraea_probe_mfma_bf16.argtypes = [i32, i32, i32, vp, i64, C.POINTER(C.c_double), vp]
         L.astraea_probe_copy.argtypes = [vp, vp, i64, vp]
+        L.astraea_check_indices.argtypes = [vp, i64, i64, vp, vp]
+        L.astraea_check_indices.restype = C.c_int
         L.astraea_attn_plan.argtypes = [i64, i32, i64, C.POINTER(i64)]
         L.astraea_attn_plan.restype = C.c_int
         L.astraea_probe_kernel_timer.argtypes = [C.c_int]
@@ -240,6 +242,11 @@ def astraea_probe_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
     nbytes = src.numel() * src.element_size()
     assert dst.numel() * dst.element_size() == nbytes
     _check(lib().astraea_probe_copy(_p(src), _p(dst), nbytes, _stream()))
+
+
+def astraea_check_indices(idx_sel: Optional[torch.Tensor], k_sel: int, N: int, counts_out: torch.Tensor) -> None:
+    assert counts_out.dtype == torch.int32 and counts_out.numel() >= 2 and counts_out.is_contiguous()
+    _check(lib().astraea_check_indices(_p(idx_sel), k_sel, N, _p(counts_out), _stream()))
 
 
 def astraea_attn_plan(N: int, H: int, k_sel: int) -> dict:

@@ -252,6 +252,17 @@ double astraea_attn_flops(int64_t N, int64_t k_sel, int32_t H, int32_t D)
     return 4.0 * (double)k_sel * (double)N * (double)D * (double)H;
 }
 
+int astraea_check_indices(const int32_t *idx_sel, int64_t k_sel, int64_t N, int32_t *counts_out, void *stream)
+{
+    if (N <= 0 || N > kMaxTokens || k_sel < 0 || k_sel > kMaxTokens)
+        return fail(ASTRAEA_ERR_INVALID, "astraea_check_indices: N=%lld, k_sel=%lld out of range", (long long)N,
+                    (long long)k_sel);
+    if (!counts_out || (k_sel > 0 && !idx_sel)) return fail(ASTRAEA_ERR_INVALID, "astraea_check_indices: NULL pointer");
+    if (((uintptr_t)idx_sel | (uintptr_t)counts_out) % 4 != 0)
+        return fail(ASTRAEA_ERR_INVALID, "astraea_check_indices: pointers must be 4-byte aligned");
+    return launch_check_indices(idx_sel, k_sel, N, counts_out, (hipStream_t)stream);
+}
+
 int astraea_attn_plan(int64_t N, int32_t H, int64_t k_sel, int64_t plan_out[8])
 {
     if (!plan_out) return fail(ASTRAEA_ERR_INVALID, "astraea_attn_plan: NULL output");

@@ -34,6 +34,8 @@ int launch_move_rows(void *dst, const void *src, int64_t row_bytes, int64_t dst_
                      int64_t src_stride_bytes, const int32_t *idx, int64_t k_sel, int64_t n_rows, bool index_dst,
                      bool index_src, hipStream_t stream);
 
+int launch_check_indices(const int32_t *idx_sel, int64_t k_sel, int64_t N, int32_t *counts, hipStream_t stream);
+
 int launch_lse_weight_update(const float *lse_sel, int32_t H, int64_t N, const int32_t *idx_sel, int64_t k_sel,
                              float *lse_weight, hipStream_t stream);
 

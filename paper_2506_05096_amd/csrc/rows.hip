@@ -65,7 +65,33 @@ __global__ __launch_bounds__(256) void lse_weight_kernel(const float *__restrict
     if ((uint64_t)tok < (uint64_t)n_rows) lse_weight[tok] = acc / (float)H;
 }
 
+// counts[0] += entries outside [0, n_rows); counts[1] += positions r >= 1 with idx[r] <= idx[r-1].
+__global__ __launch_bounds__(256) void check_indices_kernel(const int32_t *__restrict__ idx, int64_t k_sel,
+                                                            int64_t n_rows, int32_t *__restrict__ counts)
+{
+    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= k_sel) return;
+    const int32_t ix = idx[r];
+    if ((uint64_t)(int64_t)ix >= (uint64_t)n_rows) atomicAdd(&counts[0], 1);
+    if (r > 0 && ix <= idx[r - 1]) atomicAdd(&counts[1], 1);
+}
+
+__global__ void clear_counts_kernel(int32_t *counts)
+{
+    if (threadIdx.x < 2) counts[threadIdx.x] = 0;
+}
+
 }  // namespace
+
+int launch_check_indices(const int32_t *idx_sel, int64_t k_sel, int64_t N, int32_t *counts, hipStream_t stream)
+{
+    // a fill kernel, not a memset: the call may be recorded into a graph
+    hipLaunchKernelGGL(clear_counts_kernel, dim3(1), dim3(64), 0, stream, counts);
+    if (k_sel > 0)
+        hipLaunchKernelGGL(check_indices_kernel, dim3((unsigned)((k_sel + 255) / 256)), dim3(256), 0, stream, idx_sel,
+                           k_sel, N, counts);
+    return check_launch("astraea_check_indices");
+}
 
 int launch_lse_weight_update(const float *lse_sel, int32_t H, int64_t N, const int32_t *idx_sel, int64_t k_sel,
                              float *lse_weight, hipStream_t stream)

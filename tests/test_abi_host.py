@@ -277,6 +277,15 @@ def test_attention_plan_work_follows_the_budget():
     assert all(abs(cost[pct] / (unit * pct) - 1) < 0.10 for pct in cost), cost
 
 
+def test_check_indices_rejects_bad_arguments(L):
+    f = L.astraea_check_indices
+    assert f(FAKE, 5, 0, FAKE, None) == ab.ERR_INVALID
+    assert f(FAKE, -1, 10, FAKE, None) == ab.ERR_INVALID
+    assert f(None, 5, 10, FAKE, None) == ab.ERR_INVALID
+    assert f(FAKE, 5, 10, None, None) == ab.ERR_INVALID
+    assert f(FAKE + 2, 5, 10, FAKE, None) == ab.ERR_INVALID
+
+
 def test_attention_plan_rejects_bad_arguments(L):
     out = (C.c_int64 * 8)()
     assert L.astraea_attn_plan(0, 1, 1, out) == ab.ERR_INVALID

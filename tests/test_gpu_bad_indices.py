@@ -159,3 +159,26 @@ def test_sparse_linear_reads_and_writes_stay_inside_the_buffers():
     rest = np.setdiff1d(np.arange(n), idx[good])
     assert np.array_equal(got[rest], yhost[G:G + n][rest])
     assert close(got[idx[good]])
+
+
+def test_check_indices_counts_what_breaks_the_contract():
+    n = 5000
+    counts = torch.full((2,), -7, dtype=torch.int32, device=DEV)
+    good = torch.arange(0, n, 3, dtype=torch.int32)
+    ab.astraea_check_indices(good.to(DEV), good.numel(), n, counts)
+    assert counts.cpu().tolist() == [0, 0]
+    bad = good.clone()
+    bad[10], bad[11], bad[500], bad[700] = -1, n, bad[499], bad[650]       # 2 out of range; 4 order breaks, see below
+    ab.astraea_check_indices(bad.to(DEV), bad.numel(), n, counts)
+    b = bad.numpy().astype(np.int64)
+    assert counts.cpu().tolist() == [int(((b < 0) | (b >= n)).sum()), int((b[1:] <= b[:-1]).sum())]
+    assert counts.cpu().tolist()[0] == 2 and counts.cpu().tolist()[1] >= 3
+    # what astraea_select_topk emits passes
+    score = torch.rand(n, generator=torch.Generator().manual_seed(1)).to(DEV)
+    idx = torch.empty(n, dtype=torch.int32, device=DEV)
+    ws = torch.empty(ab.workspace_bytes(ab.OP_SELECT_TOPK, n), dtype=torch.uint8, device=DEV)
+    ab.astraea_select_topk(score, 1234, idx, ws)
+    ab.astraea_check_indices(idx, 1234, n, counts)
+    assert counts.cpu().tolist() == [0, 0]
+    ab.astraea_check_indices(None, 0, n, counts)                             # empty list: counts cleared
+    assert counts.cpu().tolist() == [0, 0]

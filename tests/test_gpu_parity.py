@@ -449,3 +449,45 @@ def test_kernel_timer_counts_attention_launches_and_leaves_results_alone(dtype, 
     _sync()
     assert ab.kernel_times_ms() == []
     assert np.array_equal(to_np(o0), to_np(o1))
+
+
+# ------------------------------------------------------------- determinism --
+
+def test_every_kernel_gives_the_same_bits_on_every_run():
+    """No result depends on the order in which workgroups happen to run: three runs of each call on the same
+    inputs are bit-identical (the split attention items are merged in a fixed order, the top-k compaction is by
+    index, nothing accumulates through atomics)."""
+    n, h, d, c, k_sel = 4100, 24, 128, 520, 1100           # the attention of this shape has split items
+    g = torch.Generator().manual_seed(77)
+    xc, xp = torch.randn(n, c, generator=g).bfloat16().to(DEV), torch.randn(n, c, generator=g).bfloat16().to(DEV)
+    q, k, v = (torch.randn(n, h, d, generator=g).bfloat16().to(DEV) for _ in range(3))
+    w = (torch.randn(264, h * d, generator=g) / 55.0).bfloat16().to(DEV)
+    assert ab.astraea_attn_plan(n, h, k_sel)["splits"] > 1
+    ws_t = torch.empty(ab.workspace_bytes(ab.OP_SELECT_TOPK, n), dtype=torch.uint8, device=DEV)
+    ws_a = torch.empty(ab.workspace_bytes(ab.OP_SPARSE_ATTN, n, k_sel, h, d), dtype=torch.uint8, device=DEV)
+    runs = []
+    for _ in range(3):
+        score = torch.empty(n, device=DEV)
+        idx = torch.empty(n, dtype=torch.int32, device=DEV)
+        o = torch.empty(k_sel, h, d, dtype=torch.bfloat16, device=DEV)
+        lse = torch.empty(k_sel, h, device=DEV)
+        y = torch.empty(k_sel, 264, dtype=torch.bfloat16, device=DEV)
+        ab.astraea_score(xc, xp, score)
+        ab.astraea_select_topk(score, k_sel, idx, ws_t)
+        ab.astraea_sparse_attn_fwd(q, k, v, idx, k_sel, o, 1.0 / math.sqrt(d), lse_sel=lse, workspace=ws_a)
+        ab.astraea_sparse_linear(o.view(k_sel, h * d), w, None, None, k_sel, y, act=ab.ACT_GELU_TANH, x_is_compact=True)
+        _sync()
+        runs.append([to_np(score), idx[:k_sel].cpu().numpy(), to_np(o), to_np(lse), to_np(y)])
+        ws_a.random_(0, 255)                                # nothing may depend on what the workspace held
+    for other in runs[1:]:
+        for a, b in zip(runs[0], other):
+            assert np.array_equal(a.view(np.uint8), b.view(np.uint8))
+    # the fp32 attention too
+    qf, kf, vf = (t[:, :2, :64].float().contiguous() for t in (q, k, v))
+    outs = []
+    for _ in range(3):
+        o = torch.empty(k_sel, 2, 64, device=DEV)
+        ab.astraea_sparse_attn_fwd(qf, kf, vf, torch.from_numpy(runs[0][1]).to(DEV), k_sel, o, 0.125)
+        _sync()
+        outs.append(to_np(o))
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
