@@ -177,7 +177,8 @@ def token_sparse_block(torch, ab, w, t, k, reps=5):
         blk.run(tt, k)
     torch.cuda.synchronize()
     step_ms = (time.perf_counter() - t0) * 1e3 / reps
-    fl_qkv, fl_rest = 2.0 * k * E * 3 * E, 2.0 * k * (E * E + 2 * E * hid)
+    fl = blk.flops(k)
+    fl_qkv, fl_rest = fl["qkv_proj"], fl["out_proj"] + fl["mlp"]
     lin_ms = ms["qkv_proj"] + ms["out_proj_mlp"]
     return {"ms_per_step": step_ms, "ms": ms,
             "linear_TFLOPs": (fl_qkv + fl_rest) / lin_ms / 1e9,

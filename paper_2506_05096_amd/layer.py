@@ -142,6 +142,15 @@ class TokenSparseBlock(LayerStep):
     def _b(self, name):
         return self.w.get(name)
 
+    def flops(self, k: int) -> Dict[str, float]:
+        """Multiply-add counts of one block step at k selected tokens, by the formulas of the paper's FLOPs
+        appendix with the token count N replaced by k where a layer runs on the selected tokens only (E = H*D,
+        batch 1): Q/K/V projection 6kE^2, attention scores and output 4kNE, output projection 2kE^2, the two
+        MLP layers 2 * 2kE*hidden (16kE^2 at hidden = 4E)."""
+        E, hid, N = float(self.E), float(self.hidden), float(self.N)
+        return {"qkv_proj": 6.0 * k * E * E, "attn": 4.0 * k * N * E, "out_proj": 2.0 * k * E * E,
+                "mlp": 4.0 * k * E * hid}
+
     def step_qkv(self, t: Dict[str, torch.Tensor], k: int) -> None:
         N, E, idx = self.N, self.E, self.idx_sel
         x = t["x_in"]

@@ -293,3 +293,21 @@ def test_attention_plan_rejects_bad_arguments(L):
     assert L.astraea_attn_plan(10, 1, 0, out) == ab.ERR_INVALID
     assert L.astraea_attn_plan(10, 1, 1, None) == ab.ERR_INVALID
     assert L.astraea_attn_plan(10, 1, 1, out) == ab.OK
+
+
+def test_block_flop_accounting_is_the_papers_formulas_at_k():
+    """TokenSparseBlock.flops: the FLOPs appendix (self-attention 8BNH^2 + 4BN^2H in total, MLP 16BNH^2, with the
+    paper's H = hidden width = E here) at k = N, and exactly the budget fraction of that at k < N."""
+    import torch
+    from paper_2506_05096_amd.layer import TokenSparseBlock
+    N, H, D = 1000, 4, 128
+    E = H * D
+    blk = TokenSparseBlock.__new__(TokenSparseBlock)          # accounting only: no buffers, no GPU
+    blk.N, blk.E, blk.hidden = N, E, 4 * E
+    full = blk.flops(N)
+    assert full["qkv_proj"] + full["attn"] + full["out_proj"] == 8.0 * N * E * E + 4.0 * N * N * E
+    assert full["mlp"] == 16.0 * N * E * E
+    assert full["attn"] == ab.astraea_attn_flops(N, N, H, D)
+    for pct in (10, 40, 50, 70):
+        part = blk.flops(N * pct // 100)
+        assert all(abs(part[name] / full[name] - pct / 100) < 1e-12 for name in full)

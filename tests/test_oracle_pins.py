@@ -438,6 +438,23 @@ def test_paper_flops_ratio_is_the_budget():
             assert abs(float(val) / orig - pct / 100.0) < 2e-4, name
 
 
+def test_paper_cross_and_mlp_flops_follow_the_budget():
+    """The same tables' Cross and MLP columns (Wan, OpenSora): the per-token layers cost the budget fraction of
+    the original, which is the reading behind running them on the selected rows only.  (The HunyuanVideo table
+    keeps one MLP figure for all budgets; the row is in the fixture and is checked to be exactly that.)"""
+    from pathlib import Path
+    rows = [l.split() for l in (Path(__file__).parent / "golden" / "paper_cross_mlp_flops.txt").read_text().splitlines()
+            if l.strip() and not l.startswith("#")]
+    assert len(rows) == 7
+    for name, col, orig, b40, b50, b70 in rows:
+        orig = float(orig)
+        for pct, val in ((40, b40), (50, b50), (70, b70)):
+            if name == "HunyuanVideo":
+                assert float(val) == orig
+            else:
+                assert abs(float(val) / orig - pct / 100.0) < 1.5e-3, (name, col, pct)
+
+
 # ------------------------------------------------- per-token layers on selected rows --
 
 def _bf16(t):
