@@ -178,9 +178,9 @@ int astraea_scatter_update(void *cache, const void *src, astraea_dtype dt, int64
  *            what it held: with a cached K, V or output buffer as y this is the projection fused
  *            with the cache refresh.
  *   act      ASTRAEA_ACT_NONE, or ASTRAEA_ACT_GELU_TANH: 0.5 t (1 + tanh(sqrt(2/pi) (t + 0.044715 t^3))).
- * Supported: BF16 (bf16 MFMA, fp32 accumulation, bias and activation in fp32, one rounding to bf16);
- * c_in a multiple of 64, c_out a multiple of 8, strides multiples of 8 elements, pointers 16-byte
- * aligned, x and w each spanning less than 4 GiB.  F32 returns ASTRAEA_ERR_UNSUPPORTED.
+ * BF16: bf16 MFMA, fp32 accumulation, bias and activation in fp32, one rounding to bf16; x and w must
+ * each span less than 4 GiB.  F32: fp32 MFMA, everything in fp32.  Both: c_in a multiple of 64, c_out a
+ * multiple of 8, strides multiples of 8 elements, pointers 16-byte aligned.
  * idx_sel (distinct, in [0, N)) is required unless both sides are compact.  No workspace.
  * k_sel == 0 enqueues nothing.
  */

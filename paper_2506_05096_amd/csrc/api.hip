@@ -150,7 +150,6 @@ int astraea_sparse_linear(const void *x, const void *w, const void *bias, astrae
 {
     const char *fn = "astraea_sparse_linear";
     if (!dtype_ok(dt)) return fail(ASTRAEA_ERR_UNSUPPORTED, "%s: unknown dtype %d", fn, (int)dt);
-    if (dt != ASTRAEA_BF16) return fail(ASTRAEA_ERR_UNSUPPORTED, "%s: only the bf16 path exists", fn);
     if (act != ASTRAEA_ACT_NONE && act != ASTRAEA_ACT_GELU_TANH)
         return fail(ASTRAEA_ERR_UNSUPPORTED, "%s: unknown activation %d", fn, (int)act);
     if (N <= 0 || N > kMaxTokens) return fail(ASTRAEA_ERR_INVALID, "%s: N=%lld out of range", fn, (long long)N);
@@ -163,9 +162,9 @@ int astraea_sparse_linear(const void *x, const void *w, const void *bias, astrae
         return fail(ASTRAEA_ERR_UNSUPPORTED, "%s: c_in must be a multiple of 64 and c_out of 8", fn);
     if (x_row_stride < c_in || y_row_stride < c_out || x_row_stride % 8 != 0 || y_row_stride % 8 != 0)
         return fail(ASTRAEA_ERR_INVALID, "%s: row strides must cover a row and be multiples of 8 elements", fn);
-    // the tile copies address x and w with 32-bit byte offsets
+    // the bf16 kernel's tile copies address x and w with 32-bit byte offsets
     const int64_t x_rows = x_is_compact ? k_sel : N;
-    if (x_rows * x_row_stride * 2 >= ((int64_t)1 << 32) || c_out * c_in * 2 >= ((int64_t)1 << 32))
+    if (dt == ASTRAEA_BF16 && (x_rows * x_row_stride * 2 >= ((int64_t)1 << 32) || c_out * c_in * 2 >= ((int64_t)1 << 32)))
         return fail(ASTRAEA_ERR_UNSUPPORTED, "%s: x and w must each span less than 4 GiB", fn);
     if (k_sel == 0) return ASTRAEA_OK;
     if (!x || !w || !y) return fail(ASTRAEA_ERR_INVALID, "%s: NULL tensor", fn);
@@ -173,6 +172,9 @@ int astraea_sparse_linear(const void *x, const void *w, const void *bias, astrae
     if (((uintptr_t)x | (uintptr_t)w | (uintptr_t)y | (uintptr_t)bias) % 16 != 0)
         return fail(ASTRAEA_ERR_INVALID, "%s: x, w, bias and y must be 16-byte aligned", fn);
     if ((uintptr_t)idx_sel % 4 != 0) return fail(ASTRAEA_ERR_INVALID, "%s: idx_sel must be 4-byte aligned", fn);
+    if (dt == ASTRAEA_F32)
+        return launch_linear_f32(x, w, bias, y, idx_sel, k_sel, N, (int32_t)c_in, (int32_t)c_out, x_row_stride,
+                                 y_row_stride, x_is_compact ? 0 : 1, y_is_compact ? 0 : 1, (int)act, (hipStream_t)stream);
     return launch_linear_bf16(x, w, bias, y, idx_sel, k_sel, N, (int32_t)c_in, (int32_t)c_out, x_row_stride, y_row_stride,
                               x_is_compact ? 0 : 1, y_is_compact ? 0 : 1, (int)act, (hipStream_t)stream);
 }

@@ -43,6 +43,10 @@ int launch_linear_bf16(const void *x, const void *w, const void *bias, void *y, 
                        int64_t n_rows, int32_t c_in, int32_t c_out, int64_t ldx, int64_t ldy, int x_indexed,
                        int y_indexed, int act, hipStream_t stream);
 
+int launch_linear_f32(const void *x, const void *w, const void *bias, void *y, const int32_t *idx_sel, int64_t k_sel,
+                      int64_t n_rows, int32_t c_in, int32_t c_out, int64_t ldx, int64_t ldy, int x_indexed,
+                      int y_indexed, int act, hipStream_t stream);
+
 size_t attn_bf16_workspace_bytes(int64_t N, int32_t H);
 int attn_bf16_plan(int64_t N, int32_t H, int64_t k_sel, int64_t plan[8]);
 int launch_attn_bf16_d128(const void *q, const void *k, const void *v, int64_t N, int32_t H, int64_t q_stride_n,

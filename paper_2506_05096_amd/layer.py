@@ -122,19 +122,21 @@ class TokenSparseBlock(LayerStep):
     attention, output projection, two MLP layers).  Layer norms, modulation and residual sums of a real DiT
     block are not part of the paper's algorithm and are left out.
 
-    Weights are [c_out, c_in] bf16 tensors supplied by the caller (synthetic in the tests and the benchmark).
+    Weights are [c_out, c_in] tensors of the block's dtype (bf16, or fp32 for the fp32 configuration) supplied by
+    the caller (synthetic in the tests and the benchmark).
     K and V of the selected tokens are written straight into the cached K/V by the projection (the cache
     refresh fused into its producer), the MLP's second layer writes straight into the cached block output.
     With a packed cache t["qkv_cache"] [N, 3, H, D] and a stacked weight "wqkv" [3E, E] the three projections
     are one call, and the attention reads Q, K and V through strides.
     """
 
-    def __init__(self, N: int, H: int, D: int, weights: Dict[str, torch.Tensor], device="cuda", mlp_ratio: int = 4):
-        super().__init__(N, H, D, torch.bfloat16, device)
+    def __init__(self, N: int, H: int, D: int, weights: Dict[str, torch.Tensor], device="cuda", mlp_ratio: int = 4,
+                 dtype: torch.dtype = torch.bfloat16):
+        super().__init__(N, H, D, dtype, device)
         E = H * D
         self.E, self.hidden = E, mlp_ratio * E
         self.w = weights            # wq wk wv wo [E, E]; w1 [hidden, E]; w2 [E, hidden]; optional b* biases
-        bf = dict(dtype=torch.bfloat16, device=device)
+        bf = dict(dtype=dtype, device=device)
         self.q_sel = torch.empty((N, H, D), **bf)
         self.h_sel = torch.empty((N, E), **bf)           # output projection result
         self.m_sel = torch.empty((N, self.hidden), **bf)  # MLP hidden activations

@@ -142,7 +142,7 @@ def test_sparse_linear_rejects_bad_arguments(L):
              b=None, y=FAKE):
         return f(x, w, b, dt, N, cin, cout, xs, idx, k_sel, xc, act, y, ys, yc, None)
 
-    assert call(dt=ab.F32) == ab.ERR_UNSUPPORTED                # bf16 only
+    assert call(dt=ab.F32, k_sel=0, x=None, w=None, y=None, idx=None) == ab.OK      # fp32 is a supported mode
     assert call(dt=9) == ab.ERR_UNSUPPORTED
     assert call(act=2) == ab.ERR_UNSUPPORTED
     assert call(cin=96, xs=96) == ab.ERR_UNSUPPORTED            # contraction advances in steps of 64

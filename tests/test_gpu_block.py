@@ -161,3 +161,47 @@ def test_block_with_packed_qkv_cache_equals_the_three_projection_form():
     rest[idx] = False
     assert torch.equal(tb["qkv_cache"][rest, 0], q_old[rest])                  # the others keep what they had
     assert torch.equal(tb["out_cache"], ta["out_cache"])
+
+
+def test_block_fp32_at_the_fp32_configuration():
+    """The fp32 configuration (N=4096, 8 heads of 64, feature width 512, budget 50 %): the same chain in fp32,
+    each stage from the GPU's own output of the stage before, max-abs <= 1e-4 per stage."""
+    from paper_2506_05096_amd import synth
+    wl = synth.WORKLOADS["cfg0"]
+    n, H, D, E, hid = wl.N, wl.H, wl.D, wl.H * wl.D, 4 * wl.H * wl.D
+    t = synth.make_layer_inputs(wl, seed=0, device=DEV)
+    g = torch.Generator(device=DEV).manual_seed(5)
+    mk = lambda o, i: torch.randn(o, i, device=DEV, generator=g) * i ** -0.5
+    wts = {"wq": mk(E, E), "wk": mk(E, E), "wv": mk(E, E), "wo": mk(E, E), "w1": mk(hid, E), "w2": mk(E, hid),
+           "bq": torch.randn(E, device=DEV, generator=g) * 0.1, "b1": torch.randn(hid, device=DEV, generator=g) * 0.1}
+    tt = {"x_in": t["x_cur"], "x_prev": t["x_prev"], "k_cache": t["k_cache"], "v_cache": t["v_cache"],
+          "out_cache": t["out_cache"]}
+    before = {k_: to_np(tt[k_]).reshape(n, E).copy() for k_ in ("k_cache", "v_cache", "out_cache")}
+    x_in, x_prev = to_np(tt["x_in"]), to_np(tt["x_prev"])
+    hw = {k_: to_np(v) for k_, v in wts.items()}
+    blk = TokenSparseBlock(n, H, D, wts, device=DEV, dtype=torch.float32)
+    k = blk.budget_to_k(50)
+    blk.run(tt, k)
+    torch.cuda.synchronize()
+    err = lambda got, ref: float(np.max(np.abs(got.astype(np.float64) - ref)))
+
+    e_idx, e_rem, _ = oracle.topk(oracle.score(x_in, x_prev, oracle.DELTA_L2), k)
+    assert np.array_equal(blk.idx_sel[:k].cpu().numpy(), e_idx)
+    kc, vc, out = (to_np(tt[k_]).reshape(n, E) for k_ in ("k_cache", "v_cache", "out_cache"))
+    for name, arr in (("k_cache", kc), ("v_cache", vc), ("out_cache", out)):
+        assert np.array_equal(arr[e_rem], before[name][e_rem]), name
+    q_gpu = to_np(blk.q_sel.view(n, E)[:k])
+    assert err(q_gpu, oracle.sparse_linear(x_in, hw["wq"], e_idx, bias=hw["bq"])) <= 1e-4
+    assert err(kc[e_idx], oracle.sparse_linear(x_in, hw["wk"], e_idx)) <= 1e-4
+    assert err(vc[e_idx], oracle.sparse_linear(x_in, hw["wv"], e_idx)) <= 1e-4
+    rows = np.unique(np.concatenate([[0, 1, 127, 128, k - 2, k - 1], np.random.default_rng(0).integers(0, k, 58)]))
+    o64, _ = oracle.sparse_attn(q_gpu[rows].reshape(len(rows), H, D), kc.reshape(n, H, D), vc.reshape(n, H, D), None,
+                                1.0 / math.sqrt(D), q_is_compact=True)
+    o_gpu = to_np(blk.o_sel.view(n, E)[:k])
+    assert err(o_gpu[rows], o64.reshape(len(rows), E)) <= 1e-4
+    h_gpu = to_np(blk.h_sel[:k])
+    assert err(h_gpu, oracle.sparse_linear(o_gpu, hw["wo"], None, x_is_compact=True)) <= 1e-4
+    m_gpu = to_np(blk.m_sel[:k])
+    ref = oracle.sparse_linear(h_gpu, hw["w1"], None, bias=hw["b1"], act=oracle.ACT_GELU_TANH, x_is_compact=True)
+    assert err(m_gpu, ref) <= 1e-4
+    assert err(out[e_idx], oracle.sparse_linear(m_gpu, hw["w2"], None, x_is_compact=True)) <= 1e-4

@@ -124,8 +124,61 @@ def test_sparse_linear_rejects_what_it_cannot_do():
     with pytest.raises(ab.AstraeaError) as e:
         ab.astraea_sparse_linear(x, w, None, None, 64, y, x_is_compact=True)       # c_in not a multiple of 64
     assert e.value.status == ab.ERR_UNSUPPORTED
-    xf = torch.zeros(64, 64, device=DEV)
+    xf = torch.zeros(64, 96, device=DEV)
     with pytest.raises(ab.AstraeaError) as e:
-        ab.astraea_sparse_linear(xf, torch.zeros(8, 64, device=DEV), None, None, 64, torch.zeros(64, 8, device=DEV),
-                                 x_is_compact=True)                                 # fp32 has no kernel
+        ab.astraea_sparse_linear(xf, torch.zeros(8, 96, device=DEV), None, None, 64, torch.zeros(64, 8, device=DEV),
+                                 x_is_compact=True)                                 # the same rule in fp32
     assert e.value.status == ab.ERR_UNSUPPORTED
+
+
+# ------------------------------------------------------------------- fp32 mode --
+
+@pytest.mark.parametrize("n,cin,cout,k_sel", [
+    (4096, 512, 512, 2048),     # the fp32 configuration's width and budget
+    (1000, 128, 264, 333),      # ragged in both tile directions
+    (300, 192, 1536, 257),      # one row past a token tile, several feature tiles
+    (64, 64, 8, 1),             # smallest legal shape
+    (700, 3072, 128, 130),      # long contraction
+])
+@pytest.mark.parametrize("act", [ab.ACT_NONE, ab.ACT_GELU_TANH])
+def test_sparse_linear_fp32_matches_oracle(n, cin, cout, k_sel, act):
+    """fp32 in, fp32 accumulation on the fp32 matrix instruction, fp32 out: max-abs <= 1e-4 against the fp64
+    oracle for outputs of order one (the bar of the fp32 attention)."""
+    g = torch.Generator().manual_seed(n + cout)
+    x = torch.randn(n, cin, generator=g)
+    w = torch.randn(cout, cin, generator=g) * cin ** -0.5
+    b = torch.randn(cout, generator=g)
+    idx = torch.randperm(n, generator=g)[:k_sel].sort().values.to(torch.int32)
+    ref = oracle.sparse_linear(x.numpy(), w.numpy(), idx.numpy(), bias=b.numpy(), act=act)
+    y = torch.full((k_sel, cout), float("nan"), device=DEV)
+    ab.astraea_sparse_linear(x.to(DEV), w.to(DEV), b.to(DEV), idx.to(DEV), k_sel, y, act=act)
+    torch.cuda.synchronize()
+    got = y.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(got))
+    assert np.max(np.abs(got - ref)) <= 1e-4, float(np.max(np.abs(got - ref)))
+
+
+def test_sparse_linear_fp32_row_modes_agree_and_leave_other_rows_alone():
+    n, cin, cout, k_sel, pad = 1300, 256, 200, 500, 24
+    g = torch.Generator().manual_seed(4)
+    x = torch.randn(n, cin, generator=g)
+    w = torch.randn(cout, cin, generator=g) / 16.0
+    idx = torch.randperm(n, generator=g)[:k_sel].sort().values.to(torch.int32)
+    dx, dw, di = x.to(DEV), w.to(DEV), idx.to(DEV)
+    y0 = torch.empty(k_sel, cout, device=DEV)
+    ab.astraea_sparse_linear(dx, dw, None, di, k_sel, y0)
+    y1 = torch.empty(k_sel, cout, device=DEV)
+    ab.astraea_sparse_linear(dx[di.long()].contiguous(), dw, None, None, k_sel, y1, x_is_compact=True)
+    cache0 = torch.randn(n, cout + pad, generator=g)
+    cache = cache0.to(DEV)
+    ab.astraea_sparse_linear(dx, dw, None, di, k_sel, cache[:, :cout], y_is_compact=False)
+    ab.astraea_sparse_linear(dx, dw, None, di, 0, cache[:, :cout], y_is_compact=False)      # budget 0: nothing moves
+    torch.cuda.synchronize()
+    ref = oracle.sparse_linear(x.numpy(), w.numpy(), idx.numpy())
+    assert np.max(np.abs(y0.cpu().numpy() - ref)) <= 1e-4
+    assert np.array_equal(y0.cpu().numpy(), y1.cpu().numpy())
+    got = cache.cpu().numpy()
+    assert np.array_equal(got[idx.numpy()][:, :cout], y0.cpu().numpy())
+    rest = np.setdiff1d(np.arange(n), idx.numpy())
+    assert np.array_equal(got[rest], cache0.numpy()[rest])
+    assert np.array_equal(got[:, cout:], cache0.numpy()[:, cout:])
