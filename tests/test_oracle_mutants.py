@@ -1,6 +1,6 @@
 """Do the pins notice a mistake?  Each entry of oracle_mutant_list plants one plausible mistake in a copy of the
 oracle (never in the repository's files); the pin tests then run against that copy in a child process and must
-fail.  A copy without a mistake must pass, so a failure is the pins' verdict and not the harness's.  Only pins
+fail.  A copy without a mistake must pass, so a failure comes from the pins and not from the harness.  Only pins
 are run (tests that compare the library with the oracle are deselected): the point is that the oracle is held by
 something other than the code it checks.  CPU only."""
 import concurrent.futures as cf
@@ -19,7 +19,7 @@ FILES = ("__init__.py", "astraea_oracle.c", "budget_search.py")
 
 
 def _run_pins(mutant):
-    """Returns (name, verdict): 'killed' / 'survived' / a description of a harness problem."""
+    """Returns (name, outcome): 'killed' / 'survived' / a description of a harness problem."""
     name, fname, old, new, target = mutant
     tmp = Path(tempfile.mkdtemp(prefix="oracle_mutant_"))
     try:
