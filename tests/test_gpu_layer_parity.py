@@ -119,6 +119,16 @@ def test_config3_720p_headline(fused):
     _check_step(w, t, _host(t), layer, 30, n_rows=24, tag="cfg3" + ("/fused" if fused else ""))
 
 
+@pytest.mark.parametrize("budget", [10, 100])
+def test_config3_at_the_ends_of_the_budget_range(budget):
+    """The headline shape at the smallest budget of the schedule (the launch plan with the largest share of split
+    work items) and at 100 % (dense attention for every token)."""
+    w = synth.WORKLOADS["cfg3"]
+    t = synth.make_layer_inputs(w, seed=0, device=DEV)
+    layer = LayerStep(w.N, w.H, w.D, w.torch_dtype, device=DEV)
+    _check_step(w, t, _host(t), layer, budget, n_rows=16, tag=f"cfg3@{budget}%")
+
+
 def test_config4_sweep_three_steps_with_carried_caches():
     """Budgets from the drawn schedule, fresh features / Q / K / V rows per step, caches carried over."""
     w = synth.WORKLOADS["cfg4"]
