@@ -31,18 +31,11 @@
 //    the exponentials of its own tile, so the matrix pipe and the VALU work at the same time.
 #include <type_traits>
 
-#include "common.h"
+#include "gfx950.h"
 
 namespace astraea {
 namespace {
 
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef float floatx2 __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef short short4v __attribute__((ext_vector_type(4)));
-typedef uint32_t uint2v __attribute__((ext_vector_type(2)));
-typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
 
 constexpr int D = 128;
 constexpr int kWaves = 8;
@@ -65,27 +58,6 @@ __device__ __forceinline__ float xhalf_sum(float x)
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-__device__ __forceinline__ uint32_t pack_bf16(float a, float b)
-{
-    floatx2 f = {a, b};
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));   // v_cvt_pk_bf16_f32, RNE
-}
-
-__device__ __forceinline__ bf16x8 lds_read_b128(uint32_t addr)
-{
-    return *reinterpret_cast<const bf16x8 __attribute__((address_space(3))) *>((uintptr_t)addr);
-}
-// 16 bytes per lane from global memory straight into LDS: lane l of the wave lands at
-// lds_wave_base + 16*l.  The LDS base travels in M0.  Completion is counted by vmcnt; the kernel
-// waits for it explicitly before the barrier that publishes the tile.
-__device__ __forceinline__ void dma16(const void *gbase, uint32_t goff, uint32_t lds_wave_base)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :
-                 : "s"(lds_wave_base), "v"(goff), "s"(gbase)
-                 : "memory");
-}
-__device__ __forceinline__ void wait_dma() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 
 // ---- pre-pass: V [N, H, 128] -> tiles of V^T.  Tile (head, T) is 16 KiB at
@@ -197,11 +169,8 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
     // ---- Q fragment: lane holds query column qc, head-dim 16*s + 8*hf + 0..7 (B operand of K Q^T)
     int64_t r = r0 + qc;
     if (r > k_sel - 1) r = k_sel - 1;               // ragged last tile: duplicate a valid row, never stored
-    int64_t qrow = r;
-    if (!q_is_compact) {                            // an index outside [0, N) reads a valid row instead
-        const int32_t ix = idx_sel[r];
-        qrow = ix < 0 ? 0 : (ix > N - 1 ? N - 1 : (int64_t)ix);
-    }
+    // an index outside [0, N) reads a valid row instead
+    const int64_t qrow = q_is_compact ? r : (int64_t)clamp_row(idx_sel[r], (int32_t)N);
     const __bf16 *qp = q + qrow * q_stride_n + (int64_t)head * q_stride_h + 8 * hf;
     bf16x8 qf[D / 16];
 #pragma unroll

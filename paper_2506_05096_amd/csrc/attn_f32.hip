@@ -10,12 +10,11 @@
 //
 // Workgroup = 4 waves x 32 queries; keys are swept in tiles of 32 staged in LDS.  This is the
 // accuracy-first path for small layers; the bf16 path carries the throughput.
-#include "common.h"
+#include "gfx950.h"
 
 namespace astraea {
 namespace {
 
-typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kWaves = 4;
 constexpr int kBq = 32 * kWaves;   // queries per workgroup
@@ -50,11 +49,8 @@ __global__ __launch_bounds__(kWaves *kWave) void attn_f32_kernel(
     // Q operand: lane holds query column qc, head-dim elements 2s + hf
     int64_t r = r0 + qc;
     if (r > k_sel - 1) r = k_sel - 1;                    // ragged last tile: duplicate a valid row, never stored
-    int64_t qrow = r;
-    if (!q_is_compact) {                                 // an index outside [0, N) reads a valid row instead
-        const int32_t ix = idx_sel[r];
-        qrow = ix < 0 ? 0 : (ix > N - 1 ? N - 1 : (int64_t)ix);
-    }
+    // an index outside [0, N) reads a valid row instead
+    const int64_t qrow = q_is_compact ? r : (int64_t)clamp_row(idx_sel[r], (int32_t)N);
     const float *qp = q + qrow * q_stride_n + (int64_t)head * q_stride_h;
     float qreg[D / 2];
 #pragma unroll

@@ -23,17 +23,11 @@
 //    hit in L2.
 //  * workgroup ids are mapped so that the 32 workgroups resident on one XCD form an 8 x 4 block of
 //    tiles: they stream 8 row tiles and 4 weight tiles through that XCD's L2 instead of 32 + 32.
-#include "common.h"
+#include "gfx950.h"
 
 namespace astraea {
 namespace {
 
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef float floatx2 __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef uint32_t uint2v __attribute__((ext_vector_type(2)));
-typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
 
 constexpr int kBm = 256;                 // tokens per tile
 constexpr int kBn = 256;                 // output features per tile
@@ -48,28 +42,6 @@ constexpr int kCopies = 32 / kCopyWaves; // 1 KiB copy instructions per copying 
 constexpr int kNumXcd = 8;
 constexpr int kSbM = 8, kSbN = 4;        // tiles of one XCD round: 8 token tiles x 4 feature tiles
 
-__device__ __forceinline__ uint32_t pack_bf16(float a, float b)
-{
-    floatx2 f = {a, b};
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));   // v_cvt_pk_bf16_f32, RNE
-}
-__device__ __forceinline__ int32_t clamp_row(int32_t ix, int32_t n_rows)
-{
-    return ix < 0 ? 0 : (ix > n_rows - 1 ? n_rows - 1 : ix);
-}
-__device__ __forceinline__ bf16x8 lds_read_b128(uint32_t addr)
-{
-    return *reinterpret_cast<const bf16x8 __attribute__((address_space(3))) *>((uintptr_t)addr);
-}
-// 16 bytes per lane from global memory straight into LDS: lane l lands at lds_wave_base + 16*l.
-__device__ __forceinline__ void dma16(const void *gbase, uint32_t goff, uint32_t lds_wave_base)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :
-                 : "s"(lds_wave_base), "v"(goff), "s"(gbase)
-                 : "memory");
-}
-__device__ __forceinline__ void wait_dma() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 // Waits until only the two most recent vector-memory instructions (the L2 warm-up loads) are pending:
 // the counter retires loads in order, so everything issued before them has then landed.
 __device__ __forceinline__ void wait_dma_keep2() { asm volatile("s_waitcnt vmcnt(2)" ::: "memory"); }
@@ -78,14 +50,6 @@ __device__ __forceinline__ void wait_dma_keep2() { asm volatile("s_waitcnt vmcnt
 __device__ __forceinline__ void touch_line(const void *gbase, uint32_t goff, uint32_t &sink)
 {
     asm volatile("global_load_dword %0, %1, %2" : "+v"(sink) : "v"(goff), "s"(gbase) : "memory");
-}
-
-__device__ __forceinline__ float gelu_tanh(float t)
-{
-    // 0.5 t (1 + tanh u) = t / (1 + e^(-2u)),  u = sqrt(2/pi) (t + 0.044715 t^3)
-    const float u = 0.79788456080286535588f * __builtin_fmaf(0.044715f * t, t * t, t);
-    const float e = __builtin_amdgcn_exp2f(-2.0f * 1.44269504088896340736f * u);
-    return t * __builtin_amdgcn_rcpf(1.0f + e);
 }
 
 struct LinearArgs {

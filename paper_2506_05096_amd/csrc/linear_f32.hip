@@ -14,24 +14,15 @@
 // MFMA-bound in principle (157.3 TFLOP/s fp32), in practice bound by the operand loads: each wave
 // re-reads its 64 + 64 rows from L2 (16 flops per byte).  It serves the small fp32 layers; the bf16
 // kernel carries the throughput.
-#include "common.h"
+#include "gfx950.h"
 
 namespace astraea {
 namespace {
 
-typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kWaves = 4;
 constexpr int kTile = 128;          // features and tokens per workgroup
 constexpr int kStep = 16;           // contraction indices per step
-
-__device__ __forceinline__ float gelu_tanh(float t)
-{
-    // 0.5 t (1 + tanh u) = t / (1 + e^(-2u)),  u = sqrt(2/pi) (t + 0.044715 t^3)
-    const float u = 0.79788456080286535588f * __builtin_fmaf(0.044715f * t, t * t, t);
-    const float e = __builtin_amdgcn_exp2f(-2.0f * 1.44269504088896340736f * u);
-    return t * __builtin_amdgcn_rcpf(1.0f + e);
-}
 
 struct LinearF32Args {
     const float *x;
@@ -91,11 +82,7 @@ __global__ __launch_bounds__(kWaves *kWave) void linear_f32_kernel(LinearF32Args
         wrow[b] = a.w + (int64_t)n * a.c_in + 8 * hf;
         int m = m0 + 32 * b + r;
         if (m > a.k_sel - 1) m = a.k_sel - 1;
-        int64_t row = m;
-        if (a.x_indexed) {
-            const int32_t ix = a.idx_sel[m];
-            row = ix < 0 ? 0 : (ix > a.n_rows - 1 ? a.n_rows - 1 : ix);
-        }
+        const int64_t row = a.x_indexed ? (int64_t)clamp_row(a.idx_sel[m], a.n_rows) : (int64_t)m;
         xrow[b] = a.x + row * a.ldx + 8 * hf;
     }
 
