@@ -311,3 +311,25 @@ def test_block_flop_accounting_is_the_papers_formulas_at_k():
     for pct in (10, 40, 50, 70):
         part = blk.flops(N * pct // 100)
         assert all(abs(part[name] / full[name] - pct / 100) < 1e-12 for name in full)
+
+
+def test_header_is_plain_c():
+    """The boundary is a C ABI: the header must compile as C99 with nothing but the standard headers, and a C
+    program must be able to link against the library by those declarations."""
+    import subprocess
+    import tempfile
+    hdr = ROOT / "include" / "astraea.h"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c", str(hdr)],
+                   check=True)
+    prog = ('#include "astraea.h"\n#include <stdio.h>\n'
+            'int main(void) { printf("%lld %s\\n", (long long)astraea_budget_to_k(118800, 30), astraea_status_string(0));'
+            ' return astraea_attn_flops(2, 1, 1, 1) == 8.0 ? 0 : 1; }\n')
+    with tempfile.TemporaryDirectory() as d:
+        src = Path(d) / "t.c"
+        src.write_text(prog)
+        exe = Path(d) / "t"
+        lib = ab.LIB_PATH
+        subprocess.run(["gcc", "-std=c99", "-I", str(ROOT / "include"), str(src), "-o", str(exe), str(lib),
+                        f"-Wl,-rpath,{lib.parent}", "-Wl,--allow-shlib-undefined"], check=True)
+        out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    assert out == ["35640", "ok"]
