@@ -326,6 +326,10 @@ def main() -> int:
     if w.dtype == "bf16" and w.D == 128:
         out["token_sparse_block"] = token_sparse_block(torch, ab, w, t, k)
     out["measured_peaks"] = measured_peaks(torch, ab)
+    if w.dtype == "bf16":
+        # the same box's register-resident MFMA loop on random operands: what the chip sustains under its power
+        # limit with nothing but MFMAs; the sustained clock, and with it both figures, differs from box to box
+        out["roofline"]["achieved_over_this_box_mfma_loop"] = achieved / out["measured_peaks"]["mfma_bf16_random_TFLOPs"]
     if args.context:
         out["library_context_same_gpu"] = library_context(torch, w, k)
     if not args.no_cpu_baseline:
