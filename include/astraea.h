@@ -121,6 +121,11 @@ int astraea_select_topk(const float *score, int64_t N, int64_t k, int32_t *idx_s
  *               256-byte aligned (may be NULL when that is 0).  The bf16 path stages a re-tiled
  *               copy of V there (N rounded up to 64, times H*D*2 bytes) plus 68 MB of partial
  *               results on every call; contents need not be initialised and are clobbered.
+ *               The fp32 path uses it only for a selection too small to fill the chip, which
+ *               it then cuts into key ranges (up to 8 x k_sel x H x (D + 4) floats of partial
+ *               results); there the workspace is optional: with NULL, or fewer bytes than
+ *               named, every work item sweeps all keys itself and the result is the same up
+ *               to summation order.
  * Supported: (BF16, D = 128) on bf16 MFMA with fp32 softmax and accumulation;
  * (F32, D = 64 or 128) on fp32 MFMA.  k_sel == 0 enqueues nothing.
  * Pointers must be 16-byte aligned and strides multiples of 8 elements.

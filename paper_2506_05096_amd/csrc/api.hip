@@ -118,7 +118,8 @@ static int sparse_attn_common(const char *fn, const void *q, const void *k, cons
                                      q_is_compact, softmax_scale, out, out_stride_n, scatter, lse_sel, workspace,
                                      (hipStream_t)stream);
     return launch_attn_f32(q, k, v, N, H, D, q_stride_n, q_stride_h, kv_stride_n, kv_stride_h, idx_sel, k_sel,
-                           q_is_compact, softmax_scale, out, out_stride_n, scatter, lse_sel, (hipStream_t)stream);
+                           q_is_compact, softmax_scale, out, out_stride_n, scatter, lse_sel,
+                           (uintptr_t)workspace % 256 == 0 ? workspace : nullptr, workspace_bytes, (hipStream_t)stream);
 }
 
 int astraea_sparse_attn_fwd(const void *q, const void *k, const void *v, astraea_dtype dt, int64_t N, int32_t H,
@@ -238,8 +239,13 @@ size_t astraea_workspace_bytes(int op, int64_t N, int64_t k_sel, int32_t H, int3
 {
     if (N < 0) return 0;
     if (op == ASTRAEA_OP_SELECT_TOPK) return topk_workspace_bytes(N);
-    // enough for either dtype: only the bf16 path (head_dim 128) stages anything
-    if (op == ASTRAEA_OP_SPARSE_ATTN) return D == 128 ? attn_bf16_workspace_bytes(N, H) : 0;
+    // enough for either dtype: the bf16 path (head_dim 128) stages V and partial results, the fp32 path
+    // partial results when a small selection is cut along the keys
+    if (op == ASTRAEA_OP_SPARSE_ATTN) {
+        const size_t f32 = (D == 64 || D == 128) ? attn_f32_workspace_bytes(N, H, D, k_sel) : 0;
+        const size_t bf16 = D == 128 ? attn_bf16_workspace_bytes(N, H) : 0;
+        return f32 > bf16 ? f32 : bf16;
+    }
     return 0;
 }
 

@@ -33,8 +33,10 @@ __global__ __launch_bounds__(kWaves *kWave) void attn_f32_kernel(
     const float *__restrict__ q, const float *__restrict__ k, const float *__restrict__ v, int64_t N, int32_t H,
     int64_t q_stride_n, int64_t q_stride_h, int64_t kv_stride_n, int64_t kv_stride_h,
     const int32_t *__restrict__ idx_sel, int64_t k_sel, int q_is_compact, float scale_log2e,
-    float *__restrict__ o_sel, int64_t o_stride_n, int o_scatter, float *__restrict__ lse_sel)
+    float *__restrict__ o_sel, int64_t o_stride_n, int o_scatter, float *__restrict__ lse_sel, int32_t splits,
+    int64_t tiles_per_split, float *__restrict__ partial)
 {
+    constexpr int kPartialPitch = D + 4;   // a share's row: D accumulators, running max, row sum (16-byte aligned)
     constexpr int KP = D + 2;      // K tile pitch (floats): lanes (key, d-parity) hit 64 distinct banks
     constexpr int VP = D + 8;      // V tile pitch: rows r and r+4 land 32 banks apart
     constexpr int DB = D / 32;
@@ -66,8 +68,12 @@ __global__ __launch_bounds__(kWaves *kWave) void attn_f32_kernel(
 
     const float *kb = k + (int64_t)head * kv_stride_h;
     const float *vb = v + (int64_t)head * kv_stride_h;
+    // blockIdx.z takes one of `splits` consecutive key ranges (the budget-aware launch: a small selection
+    // does not fill the chip with whole sweeps)
     const int64_t ntiles = (N + kBk - 1) / kBk;
-    for (int64_t t = 0; t < ntiles; ++t) {
+    const int64_t t_begin = (int64_t)blockIdx.z * tiles_per_split;
+    const int64_t t_end = t_begin + tiles_per_split < ntiles ? t_begin + tiles_per_split : ntiles;
+    for (int64_t t = t_begin; t < t_end; ++t) {
         const int64_t key0 = t * kBk;
         __syncthreads();
         // stage the tile: 32 rows x D floats each for K and V, 16-byte global loads
@@ -131,9 +137,24 @@ __global__ __launch_bounds__(kWaves *kWave) void attn_f32_kernel(
     }
 
     const float l_tot = xhalf_sum(l_run);
-    const float inv = 1.0f / l_tot;
     const int64_t rr = r0 + qc;
     if (rr >= k_sel) return;
+    if (splits > 1) {
+        // a key-range share: unnormalised accumulators, running max and row sum go to the workspace
+        float *pp = partial + (((int64_t)blockIdx.z * k_sel + rr) * H + head) * kPartialPitch;
+#pragma unroll
+        for (int b = 0; b < DB; ++b)
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+                *reinterpret_cast<float4 *>(pp + b * 32 + g * 8 + hf * 4) =
+                    make_float4(oacc[b][4 * g], oacc[b][4 * g + 1], oacc[b][4 * g + 2], oacc[b][4 * g + 3]);
+        if (hf == 0) {
+            pp[D] = m_run;
+            pp[D + 1] = l_tot;
+        }
+        return;
+    }
+    const float inv = 1.0f / l_tot;
     // compact output row rr, or straight into the cached buffer's row of that token
     const int64_t orow = o_scatter ? (int64_t)idx_sel[rr] : rr;
     float *op = o_sel + orow * o_stride_n + (int64_t)head * D;
@@ -150,26 +171,102 @@ __global__ __launch_bounds__(kWaves *kWave) void attn_f32_kernel(
     if (lse_sel && hf == 0) lse_sel[rr * H + head] = (m_run + log2f(l_tot)) * 0.69314718055994530942f;
 }
 
+// Combines the key-range shares: with m* = max_s m_s and w_s = 2^(m_s - m*), O = sum_s w_s O_s / sum_s w_s l_s.
+// One thread per (selected row, head, 4 head-dim elements), shares visited in order.
+template <int D>
+__global__ __launch_bounds__(256) void merge_f32_kernel(const float *__restrict__ partial, int32_t splits, int32_t H,
+                                                        int64_t k_sel, int64_t n_rows, const int32_t *__restrict__ idx_sel,
+                                                        float *__restrict__ o_sel, int64_t o_stride_n, int o_scatter,
+                                                        float *__restrict__ lse_sel)
+{
+    constexpr int Q4 = D / 4, kPartialPitch = D + 4;
+    const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t rh = id / Q4;
+    const int d4 = (int)(id % Q4) * 4;
+    if (rh >= k_sel * H) return;
+    const int64_t rr = rh / H;
+    const int head = (int)(rh % H);
+    const int64_t share = k_sel * H * (int64_t)kPartialPitch;
+    const float *base = partial + rh * kPartialPitch;
+    float m_star = -INFINITY;
+    for (int s = 0; s < splits; ++s) m_star = fmaxf(m_star, base[s * share + D]);
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    float l = 0.0f;
+    for (int s = 0; s < splits; ++s) {
+        const float *ps = base + s * share;
+        const float w = exp2f(ps[D] - m_star);
+        const float4 o = *reinterpret_cast<const float4 *>(ps + d4);
+        acc.x += w * o.x;
+        acc.y += w * o.y;
+        acc.z += w * o.z;
+        acc.w += w * o.w;
+        l += w * ps[D + 1];
+    }
+    const float inv = 1.0f / l;
+    const int64_t orow = o_scatter ? (int64_t)idx_sel[rr] : rr;
+    if (!o_scatter || (uint64_t)orow < (uint64_t)n_rows)
+        *reinterpret_cast<float4 *>(o_sel + orow * o_stride_n + (int64_t)head * D + d4) =
+            make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
+    if (lse_sel && d4 == 0) lse_sel[rh] = (m_star + log2f(l)) * 0.69314718055994530942f;
+}
+
+// Key-range shares per work item: enough workgroups for two waves per SIMD of the chip, shares of at least 8 key
+// tiles, at most 8 shares.  Large selections get 1 (no workspace, no merge).
+static int32_t f32_splits(int64_t N, int32_t H, int64_t k_sel)
+{
+    const int64_t waves = ((k_sel + kBq - 1) / kBq) * H * kWaves;
+    const int64_t ntiles = (N + kBk - 1) / kBk;
+    int64_t s = 2048 / (waves > 0 ? waves : 1);
+    if (s > ntiles / 8) s = ntiles / 8;
+    if (s > 8) s = 8;
+    return s < 2 ? 1 : (int32_t)s;
+}
+
 }  // namespace
+
+size_t attn_f32_workspace_bytes(int64_t N, int32_t H, int32_t D, int64_t k_sel)
+{
+    if (N <= 0 || H <= 0 || k_sel <= 0) return 0;
+    const int32_t s = f32_splits(N, H, k_sel);
+    return s > 1 ? (size_t)s * (size_t)k_sel * (size_t)H * (size_t)(D + 4) * sizeof(float) : 0;
+}
 
 int launch_attn_f32(const void *q, const void *k, const void *v, int64_t N, int32_t H, int32_t D, int64_t q_stride_n,
                     int64_t q_stride_h, int64_t kv_stride_n, int64_t kv_stride_h, const int32_t *idx_sel,
                     int64_t k_sel, int q_is_compact, float scale, void *o_sel, int64_t o_stride_n, int o_scatter,
-                    float *lse_sel, hipStream_t stream)
+                    float *lse_sel, void *workspace, size_t workspace_bytes, hipStream_t stream)
 {
     if (k_sel == 0) return ASTRAEA_OK;
-    dim3 grid((unsigned)((k_sel + kBq - 1) / kBq), (unsigned)H), block(kWaves * kWave);
+    // the split is an option: without a workspace of the size astraea_workspace_bytes names, every work item
+    // sweeps all keys itself
+    int32_t splits = f32_splits(N, H, k_sel);
+    if (splits > 1 && (!workspace || workspace_bytes < attn_f32_workspace_bytes(N, H, D, k_sel))) splits = 1;
+    const int64_t ntiles = (N + kBk - 1) / kBk;
+    const int64_t tps = (ntiles + splits - 1) / splits;
+    if ((int64_t)(splits - 1) * tps >= ntiles) splits = (int32_t)((ntiles + tps - 1) / tps);   // no empty share
+    float *partial = (float *)workspace;
+    dim3 grid((unsigned)((k_sel + kBq - 1) / kBq), (unsigned)H, (unsigned)splits), block(kWaves * kWave);
     const float c = scale * 1.44269504088896340736f;
     kernel_timer_begin(stream);
     if (D == 64)
         hipLaunchKernelGGL(attn_f32_kernel<64>, grid, block, 0, stream, (const float *)q, (const float *)k,
                            (const float *)v, N, H, q_stride_n, q_stride_h, kv_stride_n, kv_stride_h, idx_sel, k_sel,
-                           q_is_compact, c, (float *)o_sel, o_stride_n, o_scatter, lse_sel);
+                           q_is_compact, c, (float *)o_sel, o_stride_n, o_scatter, lse_sel, splits, tps, partial);
     else
         hipLaunchKernelGGL(attn_f32_kernel<128>, grid, block, 0, stream, (const float *)q, (const float *)k,
                            (const float *)v, N, H, q_stride_n, q_stride_h, kv_stride_n, kv_stride_h, idx_sel, k_sel,
-                           q_is_compact, c, (float *)o_sel, o_stride_n, o_scatter, lse_sel);
+                           q_is_compact, c, (float *)o_sel, o_stride_n, o_scatter, lse_sel, splits, tps, partial);
     kernel_timer_end(stream);
+    if (splits > 1) {
+        const int64_t threads = k_sel * H * (D / 4);
+        const dim3 mgrid((unsigned)((threads + 255) / 256));
+        if (D == 64)
+            hipLaunchKernelGGL(merge_f32_kernel<64>, mgrid, dim3(256), 0, stream, partial, splits, H, k_sel, N, idx_sel,
+                               (float *)o_sel, o_stride_n, o_scatter, lse_sel);
+        else
+            hipLaunchKernelGGL(merge_f32_kernel<128>, mgrid, dim3(256), 0, stream, partial, splits, H, k_sel, N, idx_sel,
+                               (float *)o_sel, o_stride_n, o_scatter, lse_sel);
+    }
     return check_launch("astraea_sparse_attn_fwd(f32)");
 }
 

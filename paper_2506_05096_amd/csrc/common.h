@@ -57,6 +57,7 @@ int launch_attn_bf16_d128(const void *q, const void *k, const void *v, int64_t N
 int launch_attn_f32(const void *q, const void *k, const void *v, int64_t N, int32_t H, int32_t D, int64_t q_stride_n,
                     int64_t q_stride_h, int64_t kv_stride_n, int64_t kv_stride_h, const int32_t *idx_sel,
                     int64_t k_sel, int q_is_compact, float scale, void *o_sel, int64_t o_stride_n, int o_scatter,
-                    float *lse_sel, hipStream_t stream);
+                    float *lse_sel, void *workspace, size_t workspace_bytes, hipStream_t stream);
+size_t attn_f32_workspace_bytes(int64_t N, int32_t H, int32_t D, int64_t k_sel);
 
 }  // namespace astraea

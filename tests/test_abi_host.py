@@ -53,7 +53,10 @@ def test_workspace_sizes(L):
     # attention workspace is linear in N (a re-tiled copy of V plus a fixed area for split items): no N x N buffer
     wa = ab.workspace_bytes(ab.OP_SPARSE_ATTN, 118800, 35640, 24, 128)
     assert 118800 * 24 * 128 * 2 <= wa <= 118800 * 24 * 128 * 2 + (80 << 20)
-    assert ab.workspace_bytes(ab.OP_SPARSE_ATTN, 4096, 2048, 8, 64) == 0          # fp32 path stages nothing
+    # fp32 path: partial results only when a small selection is cut along the keys (4 shares at the fp32
+    # configuration: 4 x k x H x (D + 4) floats), nothing once the selection fills the chip by itself
+    assert ab.workspace_bytes(ab.OP_SPARSE_ATTN, 4096, 2048, 8, 64) == 4 * 2048 * 8 * 68 * 4
+    assert ab.workspace_bytes(ab.OP_SPARSE_ATTN, 118800, 35640, 24, 64) == 0
 
 
 FAKE = 0x10000   # a non-NULL, 256-byte aligned address; rejected calls must never touch it

@@ -491,3 +491,39 @@ def test_every_kernel_gives_the_same_bits_on_every_run():
         _sync()
         outs.append(to_np(o))
     assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+
+
+# --------------------------------------------- fp32 attention: key-range shares --
+
+@pytest.mark.parametrize("n,h,d,k_sel", [(4096, 8, 64, 2048), (1000, 3, 128, 333), (2100, 1, 64, 5), (257, 2, 64, 257)])
+def test_attn_f32_key_range_shares_match_oracle_and_the_unsplit_run(n, h, d, k_sel):
+    """A small fp32 selection is cut into key ranges when a workspace is given (the fp32 configuration: 4
+    shares); without one every work item sweeps all keys.  Both must meet the fp32 bar against the oracle, also
+    when the rows go straight into a cached buffer."""
+    q, k, v, idx = _attn_case(n, h, d, k_sel, torch.float32, seed=5 * n + d)
+    scale = 1.0 / math.sqrt(d)
+    wsb = ab.workspace_bytes(ab.OP_SPARSE_ATTN, n, k_sel, h, d)
+    if (n, k_sel) != (257, 257):
+        assert wsb > 0                                      # these shapes are cut
+    eo, el = oracle.sparse_attn(to_np(q), to_np(k), to_np(v), idx.numpy(), scale)
+    dq, dk, dv, di = q.to(DEV), k.to(DEV), v.to(DEV), idx.to(DEV)
+    outs = []
+    for ws in (torch.empty(max(wsb, 1), dtype=torch.uint8, device=DEV), None):
+        o = torch.full((k_sel, h, d), float("nan"), device=DEV)
+        lse = torch.full((k_sel, h), float("nan"), device=DEV)
+        ab.astraea_sparse_attn_fwd(dq, dk, dv, di, k_sel, o, scale, lse_sel=lse, workspace=ws)
+        _sync()
+        got = o.cpu().numpy().astype(np.float64)
+        assert np.max(np.abs(got - eo)) <= 1e-4
+        assert np.max(np.abs(lse.cpu().numpy() - el)) <= 1e-4
+        outs.append(got)
+    assert np.max(np.abs(outs[0] - outs[1])) <= 2e-6        # same rows, another summation order
+    cache0 = torch.randn(n, h * d + 8, generator=torch.Generator().manual_seed(n))
+    cache = cache0.to(DEV)
+    ws = torch.empty(max(wsb, 1), dtype=torch.uint8, device=DEV)
+    ab.astraea_sparse_attn_update_fwd(dq, dk, dv, di, k_sel, cache[:, :h * d], scale, workspace=ws)
+    _sync()
+    got = cache.cpu().numpy()
+    assert np.max(np.abs(got[idx.numpy()][:, :h * d].reshape(k_sel, h, d) - eo)) <= 1e-4
+    rest = np.setdiff1d(np.arange(n), idx.numpy())
+    assert np.array_equal(got[rest], cache0.numpy()[rest]) and np.array_equal(got[:, h * d:], cache0.numpy()[:, h * d:])
