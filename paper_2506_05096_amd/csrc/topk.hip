@@ -12,6 +12,7 @@
 //      an element is selected iff key > T, or key == T and fewer than `need` equal elements
 //      precede it.  Ranks come from wavefront ballots and prefix popcounts.
 // The score array (4N bytes) stays in L2 across the five small launches; the step is latency-bound.
+// Up to 32768 scores take a single-workgroup kernel instead (one launch, keys held in LDS).
 #include "common.h"
 
 namespace astraea {
@@ -288,6 +289,127 @@ __global__ __launch_bounds__(kThreads) void topk_emit_kernel(const float *__rest
     }
 }
 
+// ---- small inputs: the whole selection in one workgroup and one launch.  Up to kSmallMax keys live in LDS
+// (128 KiB of the CU's 160); the three radix passes, the digit search and the ordered emit are the steps of
+// the kernels above with workgroup barriers where those have launches.  Thread t owns the contiguous
+// elements [t*items, (t+1)*items), so ranks follow index order; a thread adds a run of equal digits with one
+// LDS atomic, which keeps tightly clustered scores (all of them in one or two bins) from serialising.
+constexpr int kSmallMax = 32768;
+constexpr int kSmallThreads = 1024;
+
+__global__ __launch_bounds__(kSmallThreads) void topk_small_kernel(const float *__restrict__ score, int32_t N, uint32_t k,
+                                                                   int32_t *__restrict__ idx_sel,
+                                                                   int32_t *__restrict__ idx_remain,
+                                                                   uint8_t *__restrict__ sel_mask,
+                                                                   int32_t *__restrict__ skip_count)
+{
+    __shared__ uint32_t keys[kSmallMax];
+    __shared__ uint32_t hist[kBins];
+    __shared__ uint32_t wt_a[kSmallThreads / kWave], wt_b[kSmallThreads / kWave];
+    __shared__ uint32_t s_prefix, s_mask, s_krem;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    const int items = ((N + kSmallThreads - 1) / kSmallThreads) | 1;    // odd: a thread's walk through its elements is free of bank conflicts
+    const int first = tid * items;
+    const int last = first + items < N ? first + items : N;         // this thread's elements: [first, last)
+    for (int i = tid; i < N; i += kSmallThreads) keys[i] = score_key(score[i]);
+    if (tid == 0) {
+        s_prefix = k ? 0u : 0xffffffffu;       // k == 0: a threshold no key reaches, nothing is selected
+        s_mask = 0;
+        s_krem = k;
+    }
+    __syncthreads();
+    if (k > 0) {
+        for (int pass = 0; pass < kNumPass; ++pass) {
+            const int shift = kShift[pass];
+            const uint32_t nb = 1u << kBits[pass];
+            for (int i = tid; i < kBins; i += kSmallThreads) hist[i] = 0;
+            __syncthreads();
+            const uint32_t prefix = s_prefix, mask = s_mask, k_rem = s_krem;
+            uint32_t run_bin = 0, run_len = 0;
+            for (int i = first; i < last; ++i) {
+                const uint32_t key = keys[i];
+                if ((key & mask) != prefix) continue;
+                const uint32_t b = (key >> shift) & (nb - 1);
+                if (run_len && b != run_bin) {
+                    atomicAdd(&hist[run_bin], run_len);
+                    run_len = 0;
+                }
+                run_bin = b;
+                ++run_len;
+            }
+            if (run_len) atomicAdd(&hist[run_bin], run_len);
+            __syncthreads();
+            // the digit: walking the bins from the largest down, the first whose running count reaches k_rem.
+            // Thread t owns bins nb-1 - (t*per + j), j < per (per = 2 or 1).
+            const uint32_t per = nb / kSmallThreads;
+            uint32_t cnt[2] = {0, 0}, mine = 0;
+            for (uint32_t j = 0; j < per; ++j) {
+                cnt[j] = hist[nb - 1 - (tid * per + j)];
+                mine += cnt[j];
+            }
+            uint32_t incl = mine;
+#pragma unroll
+            for (int d = 1; d < kWave; d <<= 1) {
+                const uint32_t o = __shfl_up(incl, d);
+                if (lane >= d) incl += o;
+            }
+            if (lane == kWave - 1) wt_a[wv] = incl;
+            __syncthreads();
+            uint32_t run = incl - mine;
+            for (int w = 0; w < wv; ++w) run += wt_a[w];
+            for (uint32_t j = 0; j < per; ++j) {
+                const uint32_t b = nb - 1 - (tid * per + j);
+                if (run < k_rem && run + cnt[j] >= k_rem) {          // true for exactly one bin of one thread
+                    s_prefix = prefix | (b << shift);
+                    s_mask = mask | ((nb - 1) << shift);
+                    s_krem = k_rem - run;
+                }
+                run += cnt[j];
+            }
+            __syncthreads();
+        }
+    }
+    // ordered emit, as in topk_emit_kernel
+    const uint32_t T = s_prefix, need = s_krem;
+    uint32_t mg = 0, me = 0;
+    for (int i = first; i < last; ++i) {
+        mg += keys[i] > T;
+        me += keys[i] == T;
+    }
+    uint32_t ig = mg, ie = me;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const uint32_t og = __shfl_up(ig, d), oe = __shfl_up(ie, d);
+        if (lane >= d) {
+            ig += og;
+            ie += oe;
+        }
+    }
+    if (lane == kWave - 1) {
+        wt_a[wv] = ig;
+        wt_b[wv] = ie;
+    }
+    __syncthreads();
+    uint32_t g_before = ig - mg, e_before = ie - me;
+    for (int w = 0; w < wv; ++w) {
+        g_before += wt_a[w];
+        e_before += wt_b[w];
+    }
+    for (int i = first; i < last; ++i) {
+        const bool g = keys[i] > T, e = keys[i] == T;
+        const uint32_t sel_before = g_before + (e_before < need ? e_before : need);
+        const bool sel = g || (e && e_before < need);
+        if (sel)
+            idx_sel[sel_before] = i;
+        else if (idx_remain)
+            idx_remain[i - sel_before] = i;
+        if (sel_mask) sel_mask[i] = sel ? 1 : 0;
+        if (skip_count) skip_count[i] = sel ? 0 : skip_count[i] + 1;
+        g_before += g;
+        e_before += e;
+    }
+}
+
 }  // namespace
 
 size_t topk_workspace_bytes(int64_t N)
@@ -301,6 +423,11 @@ int launch_select_topk(const float *score, int64_t N, int64_t k, int32_t *idx_se
                        uint8_t *sel_mask, int32_t *skip_count, void *workspace, hipStream_t stream)
 {
     if (N == 0) return ASTRAEA_OK;
+    if (N <= kSmallMax) {
+        hipLaunchKernelGGL(topk_small_kernel, dim3(1), dim3(kSmallThreads), 0, stream, score, (int32_t)N, (uint32_t)k,
+                           idx_sel, idx_remain, sel_mask, skip_count);
+        return check_launch("astraea_select_topk");
+    }
     const unsigned nblk = (unsigned)((N + kChunk - 1) / kChunk);
     SelectState *st = reinterpret_cast<SelectState *>(workspace);
     uint32_t *hist = reinterpret_cast<uint32_t *>((char *)workspace + ws_hist_off());
