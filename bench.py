@@ -24,9 +24,69 @@ if str(ROOT) not in sys.path:
 METRIC = "selected-token attn TFLOP/s (% MFMA peak) + ms/layer, N=118800 H=24 D=128"
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}     # MI355X dense MFMA peaks
 PEAK_HBM_GBS = 8000.0
-# HBM bytes one launch of the dominant kernel moves, from rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by
-# what the same counter reads for the library's plain 1 GiB copy (profiles/hot_path_cfg3_hbm_traffic_and_mfma.txt).
-MEASURED_TRAFFIC_BYTES = {("cfg3", 30): 8.17e9 + 0.251e9}
+TRAFFIC_PROFILE = ROOT / "profiles" / "hot_path_cfg3_hbm_traffic_and_mfma.txt"
+_CSRC = ROOT / "paper_2506_05096_amd" / "csrc"
+KERNEL_SOURCE = {"attn_bf16_kernel": (_CSRC / "attn_bf16.hip", _CSRC / "gfx950.h")}
+
+
+def kernel_source_hash(kernel: str) -> str:
+    """First 16 hex digits of the SHA-256 of the kernel's source files, in the order listed above."""
+    import hashlib
+    h = hashlib.sha256()
+    for f in KERNEL_SOURCE[kernel]:
+        h.update(f.read_bytes())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(kernel: str, workload: str, budget: int):
+    """HBM bytes one launch of the dominant kernel moves, as the tracked rocprofv3 summary recorded them
+    (FETCH_SIZE + WRITE_SIZE, each scaled by what the same counter reads for the library's plain 1 GiB copy).
+    The summary carries a line
+        roofline_traffic kernel=<name> workload=<cfg> budget_pct=<p> fetched_bytes=<f> written_bytes=<w> source_sha256_16=<h>
+    where <h> is kernel_source_hash() of the kernel's source files at the time of the profile.  Returns (bytes, note); bytes is
+    None when there is no line for this workload or when the kernel source has changed since (a stale figure
+    would say nothing about the kernel being timed)."""
+    import re
+    if not TRAFFIC_PROFILE.exists() or kernel not in KERNEL_SOURCE:
+        return None, "no counter profile for this kernel"
+    now = kernel_source_hash(kernel)
+    for line in TRAFFIC_PROFILE.read_text().splitlines():
+        m = re.search(r"roofline_traffic kernel=(\S+) workload=(\S+) budget_pct=(\d+) fetched_bytes=(\S+) "
+                      r"written_bytes=(\S+) source_sha256_16=(\S+)", line)
+        if m and m.group(1) == kernel and m.group(2) == workload and int(m.group(3)) == budget:
+            if m.group(6) != now:
+                return None, (f"{TRAFFIC_PROFILE.name} was recorded for another version of {KERNEL_SOURCE[kernel][0].name} "
+                              f"({m.group(6)}, now {now}): rerun the FETCH_SIZE / WRITE_SIZE passes")
+            return float(m.group(4)) + float(m.group(5)), f"read from profiles/{TRAFFIC_PROFILE.name} (kernel source {now})"
+    return None, f"profiles/{TRAFFIC_PROFILE.name} has no counters for {workload} at {budget} %"
+
+
+def budget_sweep(torch, layer, t, levels=tuple(range(10, 101, 10)), reps=2):
+    """Config 4 in short, inside the default run: `reps` timed layer-steps at every budget level on the resident
+    inputs, and how far the per-step time is from a line through the origin (the paper's "latency increases
+    linearly with the computation budget").  bench.py --sweep runs the drawn 50-step schedule with fresh inputs."""
+    import numpy as np
+    ms = {}
+    for pct in levels:
+        k = layer.budget_to_k(pct)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(reps):
+            layer.run(t, k)
+        b.record()
+        torch.cuda.synchronize()
+        ms[pct] = a.elapsed_time(b) / reps
+    x = np.array(sorted(ms), float)
+    y = np.array([ms[int(p)] for p in x], float)
+    slope = float((x * y).sum() / (x * x).sum())            # least-squares line through the origin
+    dev = np.abs(y - slope * x) / (slope * x)
+    return {"ms_by_budget": {str(int(p)): float(v) for p, v in zip(x, y)}, "ms_per_percent": slope,
+            "max_rel_dev_from_linear": float(dev.max()), "at_budget_pct": int(x[int(dev.argmax())]),
+            "mean_rel_dev_from_linear": float(dev.mean()), "dense_step_ms": float(y[-1]),
+            "steps_per_level": reps,
+            "what": "whole layer-step (score + top-k + K/V refresh + attention + scatter) at each budget level, "
+                    "deviation from the least-squares line through the origin"}
 
 
 def _np(t):
@@ -202,9 +262,14 @@ def main() -> int:
     ap.add_argument("--sweep", action="store_true", help="config 4: 50-step budget schedule")
     ap.add_argument("--context", action="store_true",
                     help="also time the vendor-library GEMM and flash attention PyTorch dispatches to (context only)")
+    ap.add_argument("--source-hash", action="store_true",
+                    help="print the hash of the dominant kernel's sources that a counter profile must carry, and exit")
     ap.add_argument("--calibrate", action="store_true",
                     help="only run the measurement aids: 1 GiB plain copy (x3) and the MFMA loop")
     args = ap.parse_args()
+    if args.source_hash:
+        print(kernel_source_hash("attn_bf16_kernel"))
+        return 0
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1",
               file=sys.stderr)
@@ -293,6 +358,8 @@ def main() -> int:
     }
     peak = PEAK_TFLOPS[w.dtype]
     achieved = flops / kernel_ms / 1e9
+    kernel_name = "attn_bf16_kernel" if w.dtype == "bf16" else "attn_f32_kernel"
+    traffic, traffic_note = measured_traffic(kernel_name, w.name, budget)
     out = {
         "metric": METRIC,
         "value": flops / wall_ms / 1e9,
@@ -310,9 +377,9 @@ def main() -> int:
                                f"latent={'x'.join(map(str, w.latent))}",
                    "value_definition": "4*k*N*D*H flops / ms_per_step (whole hot path)", "seed": args.seed},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                     "frac": achieved / peak, "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, budget)),
+                     "frac": achieved / peak, "traffic": traffic, "traffic_source": traffic_note,
                      "traffic_unit": "bytes per launch (algorithmic: (2k+2N)*H*D*2 = %.3g)" % ((2 * k + 2 * w.N) * row_bytes),
-                     "kernel": "attn_bf16_kernel" if w.dtype == "bf16" else "attn_f32_kernel",
+                     "kernel": kernel_name,
                      "kernel_ms": kernel_ms, "call_ms": attn_ms, "flops_per_launch": flops,
                      "timed": "HIP events recorded by the library on the launch stream around the kernel alone, "
                               "mean over the timed steps; call_ms = the whole astraea_sparse_attn_fwd call "
@@ -323,6 +390,8 @@ def main() -> int:
         "hbm_GBps": gbs,
         "hbm_frac_of_8TBps": {k_: v_ / PEAK_HBM_GBS for k_, v_ in gbs.items()},
     }
+    if w.name in ("cfg3", "cfg4"):
+        out["budget_sweep"] = budget_sweep(torch, layer, t)
     if w.dtype == "bf16" and w.D == 128:
         out["token_sparse_block"] = token_sparse_block(torch, ab, w, t, k)
     out["measured_peaks"] = measured_peaks(torch, ab)

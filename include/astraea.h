@@ -241,10 +241,15 @@ int astraea_search_repair(int32_t *theta, int32_t T, int64_t budget_tenths, uint
  * astraea_lse_weight_update - carries the softmax by-product S_LSE of the selection metric to the
  * next timestep (Sec. 3.2 "Selection Metric": S_sig = S_LSE,t-1 * Delta_token,t, where S_LSE is the
  * row sum of exponentials the softmax computes anyway).  For every selected token
- *     lse_weight[idx_sel[r]] = (1/H) * sum_h exp(lse_sel[r, h] - ln N),
- * the mean over heads of the row's mean exponential (the paper does not say how heads combine; the
- * 1/N keeps the value near 1 and does not change any ranking).  Tokens not selected keep the weight
- * of the last step they were computed in.  The sum runs over h ascending in fp32.
+ *     lse_weight[idx_sel[r]] = (1/H) * sum_h exp(min(lse_sel[r, h] - ln N, 64)),
+ * the mean over heads of the row's mean exponential (the paper does not say how heads combine).  The
+ * 1/N keeps the value near 1; it is the same as dividing w_alpha by N, so it changes no ranking while
+ * the score is w_alpha * S_sig alone and does weigh S_sig against the penalty term w_beta * e^{n_i}
+ * once counters are used: choose w_alpha for this scaling.  The exponent is capped at 64: a head whose
+ * logits leave the range of the fp32 exponential contributes e^64 instead of infinity, so the weight
+ * and the score it multiplies stay finite (beyond that point heads are no longer told apart).
+ * Tokens not selected keep the weight of the last step they were computed in.  The sum runs over h
+ * ascending in fp32.
  *   lse_sel     [k_sel, H] fp32, as written by astraea_sparse_attn_fwd.
  *   lse_weight  [N] fp32 in/out, the array astraea_score reads.
  */

@@ -373,7 +373,10 @@ int oracle_round_to_dtype(const double *src, int64_t n, int dtype, void *dst)
 /*
  * Per-token S_LSE carried to the next step (Sec. 3.2 "Selection Metric"; the softmax row sum is the
  * by-product the paper reuses).  Reading taken for H heads: the mean over heads of the mean
- * exponential, weight[idx[r]] = (1/H) sum_h exp(lse[r,h] - ln N); evaluated in fp64, stored as fp32.
+ * exponential, weight[idx[r]] = (1/H) sum_h exp(min(lse[r,h] - ln N, 64)); evaluated in fp64, stored as
+ * fp32.  The paper's S_LSE is a plain sum of exponentials, which has no finite fp32 value once a logit
+ * passes ~88; the exponent is therefore capped at 64 (a head's mean exponential saturates at e^64), so
+ * that the weight, and the score it multiplies, stay finite and ordered.
  */
 int oracle_lse_weight_update(const double *lse_sel, int32_t H, int64_t N, const int32_t *idx_sel, int64_t k_sel,
                              float *lse_weight)
@@ -383,7 +386,7 @@ int oracle_lse_weight_update(const double *lse_sel, int32_t H, int64_t N, const 
     for (int64_t r = 0; r < k_sel; ++r) {
         double acc = 0.0;
         for (int32_t h = 0; h < H; ++h)
-            acc += exp(lse_sel[r * H + h] - log((double)N));
+            acc += exp(fmin(lse_sel[r * H + h] - log((double)N), 64.0));
         if (idx_sel[r] < 0 || idx_sel[r] >= N)
             return -1;
         lse_weight[idx_sel[r]] = (float)(acc / (double)H);

@@ -224,11 +224,29 @@ static int32_t f32_splits(int64_t N, int32_t H, int64_t k_sel)
 
 }  // namespace
 
-size_t attn_f32_workspace_bytes(int64_t N, int32_t H, int32_t D, int64_t k_sel)
+// Partial-result bytes the key-range split needs at exactly k_sel selected queries (0 when it is not cut).
+static size_t f32_partial_bytes(int64_t N, int32_t H, int32_t D, int64_t k_sel)
 {
     if (N <= 0 || H <= 0 || k_sel <= 0) return 0;
     const int32_t s = f32_splits(N, H, k_sel);
     return s > 1 ? (size_t)s * (size_t)k_sel * (size_t)H * (size_t)(D + 4) * sizeof(float) : 0;
+}
+
+// What astraea_workspace_bytes names: enough for every selection of up to k_sel queries.  The need is not
+// monotone in k_sel (fewer queries are cut into more shares), so a buffer sized once for the largest budget
+// must cover the smaller ones too: the maximum over k' <= k_sel.  Within one count of query tiles the share
+// count is fixed and the need grows with k', so only tile multiples (and k_sel itself) are candidates, and
+// past 2048 waves nothing is cut any more.
+size_t attn_f32_workspace_bytes(int64_t N, int32_t H, int32_t D, int64_t k_sel)
+{
+    if (N <= 0 || H <= 0 || k_sel <= 0) return 0;
+    size_t need = f32_partial_bytes(N, H, D, k_sel);
+    const int64_t t_max = 2048 / ((int64_t)H * kWaves) + 1;
+    for (int64_t t = 1; t <= t_max && t * kBq <= k_sel; ++t) {
+        const size_t b = f32_partial_bytes(N, H, D, t * kBq);
+        if (b > need) need = b;
+    }
+    return need;
 }
 
 int launch_attn_f32(const void *q, const void *k, const void *v, int64_t N, int32_t H, int32_t D, int64_t q_stride_n,
@@ -240,7 +258,7 @@ int launch_attn_f32(const void *q, const void *k, const void *v, int64_t N, int3
     // the split is an option: without a workspace of the size astraea_workspace_bytes names, every work item
     // sweeps all keys itself
     int32_t splits = f32_splits(N, H, k_sel);
-    if (splits > 1 && (!workspace || workspace_bytes < attn_f32_workspace_bytes(N, H, D, k_sel))) splits = 1;
+    if (splits > 1 && (!workspace || workspace_bytes < f32_partial_bytes(N, H, D, k_sel))) splits = 1;
     const int64_t ntiles = (N + kBk - 1) / kBk;
     const int64_t tps = (ntiles + splits - 1) / splits;
     if ((int64_t)(splits - 1) * tps >= ntiles) splits = (int32_t)((ntiles + tps - 1) / tps);   // no empty share

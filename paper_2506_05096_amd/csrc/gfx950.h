@@ -26,15 +26,19 @@ __device__ __forceinline__ bf16x8 lds_read_b128(uint32_t addr)
 }
 
 // 16 bytes per lane from global memory straight into LDS: lane l of the wave lands at
-// lds_wave_base + 16*l.  The LDS base travels in M0.  Completion is counted by vmcnt; a kernel
-// waits for it explicitly before the barrier that publishes the tile.
+// lds_wave_base + 16*l.  The LDS base travels in M0, which the statement overwrites (declared, so the
+// compiler keeps nothing of its own there across it).  Completion is counted by vmcnt; a kernel waits
+// for it explicitly before the barrier that publishes the tile.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"    // m0 is a reserved register; naming it as clobbered is the point
 __device__ __forceinline__ void dma16(const void *gbase, uint32_t goff, uint32_t lds_wave_base)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
                  : "s"(lds_wave_base), "v"(goff), "s"(gbase)
-                 : "memory");
+                 : "memory", "m0");
 }
+#pragma clang diagnostic pop
 __device__ __forceinline__ void wait_dma() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // An index from a caller's idx_sel, forced into [0, n_rows): reads through it stay inside the buffer.

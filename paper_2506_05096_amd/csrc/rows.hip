@@ -52,7 +52,8 @@ __global__ __launch_bounds__(kRowsPerBlock *kWave) void move_rows_kernel(
     if (p < nvec) d[p] = load_once(s + p);
 }
 
-// lse_weight[idx[r]] = mean over heads of exp(lse[r, h] - ln N); one thread per selected token.
+// lse_weight[idx[r]] = mean over heads of exp(min(lse[r, h] - ln N, 64)); one thread per selected token.
+// The cap keeps the weight finite when a head's logits leave the range of the fp32 exponential.
 __global__ __launch_bounds__(256) void lse_weight_kernel(const float *__restrict__ lse_sel, int32_t H, float log_n,
                                                          const int32_t *__restrict__ idx, int64_t k_sel, int64_t n_rows,
                                                          float *__restrict__ lse_weight)
@@ -60,7 +61,7 @@ __global__ __launch_bounds__(256) void lse_weight_kernel(const float *__restrict
     const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (r >= k_sel) return;
     float acc = 0.0f;
-    for (int h = 0; h < H; ++h) acc += expf(lse_sel[r * H + h] - log_n);
+    for (int h = 0; h < H; ++h) acc += expf(fminf(lse_sel[r * H + h] - log_n, 64.0f));
     const int64_t tok = idx[r];
     if ((uint64_t)tok < (uint64_t)n_rows) lse_weight[tok] = acc / (float)H;
 }

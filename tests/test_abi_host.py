@@ -54,9 +54,16 @@ def test_workspace_sizes(L):
     wa = ab.workspace_bytes(ab.OP_SPARSE_ATTN, 118800, 35640, 24, 128)
     assert 118800 * 24 * 128 * 2 <= wa <= 118800 * 24 * 128 * 2 + (80 << 20)
     # fp32 path: partial results only when a small selection is cut along the keys (4 shares at the fp32
-    # configuration: 4 x k x H x (D + 4) floats), nothing once the selection fills the chip by itself
+    # configuration: 4 x k x H x (D + 4) floats).  A selection that fills the chip by itself is not cut, but
+    # the size named for k_sel also serves every smaller selection (which may be cut into more shares), so a
+    # buffer sized once for the largest budget works at all of them: it never shrinks as k_sel grows, and
+    # it stays a few MB (at most 2048 waves' worth of partial rows)
     assert ab.workspace_bytes(ab.OP_SPARSE_ATTN, 4096, 2048, 8, 64) == 4 * 2048 * 8 * 68 * 4
-    assert ab.workspace_bytes(ab.OP_SPARSE_ATTN, 118800, 35640, 24, 64) == 0
+    for n, h, d in ((4096, 8, 64), (8192, 8, 64), (118800, 24, 64), (700, 3, 128)):
+        sizes = [ab.workspace_bytes(ab.OP_SPARSE_ATTN, n, k, h, d) for k in range(1, n + 1, max(1, n // 97))]
+        assert all(a <= b for a, b in zip(sizes, sizes[1:])), (n, h, d)
+        assert sizes[-1] <= 8 * 65536 * (d + 4) * 4, (n, h, d)
+    assert ab.workspace_bytes(ab.OP_SPARSE_ATTN, 118800, 35640, 24, 64) == 7 * 384 * 24 * 68 * 4     # 3 query tiles x 7 shares
 
 
 FAKE = 0x10000   # a non-NULL, 256-byte aligned address; rejected calls must never touch it

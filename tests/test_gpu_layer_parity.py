@@ -3,15 +3,18 @@ configuration bench.py times (paper_2506_05096_amd.layer.LayerStep).
 
 Config 0 is checked in full.  At the larger configurations the oracle recomputes every score, every
 selected index, every refreshed K/V row and every untouched cache row, and the attention output on a
-sample of selected rows (rows are independent: each is an exact softmax row over all N keys), always
-including the first and last selected token and rows of the last, partially filled query tile.
+sample of selected rows (rows are independent: each is an exact softmax row over all N keys): the first and
+last selected token, both sides of the last query-tile edges (the last tile is partly filled), rows of
+work items that the budget-aware launch cuts into key ranges, and random ones.  bf16 results must be within
+relative L2 1e-2 of the oracle over the whole sample and for every (row, head) by itself.
 """
 import numpy as np
 import pytest
 import torch
 
 import oracle
-from conftest import bf16_bits_to_f64, to_np
+from conftest import assert_rel_l2, bf16_bits_to_f64, to_np
+from paper_2506_05096_amd import binding as ab
 from paper_2506_05096_amd import synth
 from paper_2506_05096_amd.layer import LayerStep
 
@@ -23,16 +26,48 @@ def _f64(a):
     return bf16_bits_to_f64(a) if a.dtype == np.uint16 else a.astype(np.float64)
 
 
-def _sample_rows(k, n_rows, seed):
-    """Positions in the selected list: ends, the ragged tail of the last 256-query tile, and random ones."""
+Q_TILE = 256        # selected queries per work item of the bf16 attention launch
+
+
+def _split_item_rows(n, H, k):
+    """Positions (in the selected list) whose query tile belongs, for at least one head, to a work item that the
+    launch plan cuts into key ranges: work items are (head, query tile) pairs, head-major, XCD x owns items
+    [x * items_per_xcd, (x + 1) * items_per_xcd) and the items past the first full_items of each XCD are cut."""
+    plan = ab.astraea_attn_plan(n, H, k)
+    rows = set()
+    if plan["splits"] > 1:
+        for xcd in range(8):
+            for item in range(xcd * plan["items_per_xcd"] + plan["full_items"], (xcd + 1) * plan["items_per_xcd"]):
+                if item < H * plan["q_tiles"]:
+                    qt = item % plan["q_tiles"]
+                    rows.update(r for r in (qt * Q_TILE, qt * Q_TILE + 97, qt * Q_TILE + Q_TILE - 1) if r < k)
+    return sorted(rows)
+
+
+def _sample_rows(n, H, k, n_rows, seed, bf16):
+    """Positions in the selected list: the ends, both sides of the last three query-tile edges, a few rows of the
+    work items the launch cuts along the keys, and random ones up to n_rows."""
     rng = np.random.default_rng(seed)
-    fixed = {0, 1, k - 1, k - 2, (k // 256) * 256 - 1, (k // 256) * 256, min(k - 1, (k // 256) * 256 + 1)}
+    fixed = {0, 1, k - 2, k - 1}
+    last_edge = (k // Q_TILE) * Q_TILE
+    for e in (last_edge, last_edge - Q_TILE, last_edge - 2 * Q_TILE):
+        fixed.update((e - 1, e, e + 1))
+    if bf16:
+        split = _split_item_rows(n, H, k)
+        if split:
+            fixed.update(int(r) for r in rng.choice(split, size=min(len(split), 12), replace=False))
     fixed = {r for r in fixed if 0 <= r < k}
-    extra = rng.choice(k, size=min(k, max(0, n_rows - len(fixed))), replace=False)
+    pool = np.setdiff1d(np.arange(k), np.fromiter(fixed, dtype=np.int64), assume_unique=False)
+    extra = rng.choice(pool, size=min(len(pool), max(0, n_rows - len(fixed))), replace=False)
     return np.array(sorted(fixed | set(int(e) for e in extra)), dtype=np.int64)
 
 
-def _check_step(w, t, host, layer, budget_pct, n_rows, tag, out_known=None):
+# oracle attention rows already computed in this session, for cases that run the same inputs twice
+# (the fused and the unfused step): keyed by the caller, checked against the indices before reuse
+_ORACLE_ROWS = {}
+
+
+def _check_step(w, t, host, layer, budget_pct, n_rows, tag, out_known=None, reuse_key=None):
     """Runs one layer step on the GPU and checks it against the oracle.  `host` holds numpy copies of the
     inputs as they were before the step (all drawn by the seeded generators or computed by the oracle);
     `out_known` marks the rows of host["out_cache"] whose value is known that way (None: all of them).
@@ -67,19 +102,22 @@ def _check_step(w, t, host, layer, budget_pct, n_rows, tag, out_known=None):
         assert np.array_equal(got[e_idx], to_np(layer.o_sel[:k]).reshape(k, E)), f"{tag}: scatter positions"
 
     # attention on the sampled rows against the oracle
-    rows = np.arange(k) if n_rows >= k else _sample_rows(k, n_rows, seed=n + k)
-    o64, _ = oracle.sparse_attn(host["q"], kc.reshape(n, H, D), vc.reshape(n, H, D), e_idx[rows], layer.scale)
+    rows = np.arange(k) if n_rows >= k else _sample_rows(n, H, k, n_rows, seed=n + k, bf16=w.dtype == "bf16")
+    cached = _ORACLE_ROWS.get(reuse_key) if reuse_key else None
+    if cached is not None and np.array_equal(cached[0], e_idx[rows]):
+        o64 = cached[1]        # same inputs, same indices (all checked bit for bit above): the same oracle rows
+    else:
+        o64, _ = oracle.sparse_attn(host["q"], kc.reshape(n, H, D), vc.reshape(n, H, D), e_idx[rows], layer.scale)
+        if reuse_key:
+            _ORACLE_ROWS[reuse_key] = (e_idx[rows].copy(), o64)
     g64 = _f64(got[e_idx[rows]]).reshape(len(rows), H, D)
     assert np.all(np.isfinite(g64))
     if w.dtype == "f32":
         err = float(np.max(np.abs(g64 - o64)))
         assert err <= 1e-4, f"{tag}: max abs error {err}"
     else:
-        err = float(np.linalg.norm((g64 - o64).ravel()) / np.linalg.norm(o64.ravel()))
-        assert err <= 1e-2, f"{tag}: relative L2 error {err}"
-        worst = np.max(np.linalg.norm((g64 - o64).reshape(len(rows), -1), axis=1) /
-                       np.linalg.norm(o64.reshape(len(rows), -1), axis=1))
-        assert worst <= 2e-2, f"{tag}: worst row relative L2 {worst}"
+        err, worst = assert_rel_l2(g64, o64, tag=tag)       # whole sample, and every (row, head) by itself
+        print(f"{tag}: worst (row, head) relative L2 {worst:.3g}", flush=True)
     print(f"{tag}: N={n} k={k} rows checked={len(rows)} err={err:.3g}", flush=True)
     return kc, vc, e_idx
 
@@ -100,7 +138,7 @@ def test_config1_bf16_key_bias(budget):
     w = synth.WORKLOADS["cfg1"]
     t = synth.make_layer_inputs(w, seed=0, device=DEV)
     layer = LayerStep(w.N, w.H, w.D, w.torch_dtype, device=DEV)
-    _check_step(w, t, _host(t), layer, budget, n_rows=48, tag=f"cfg1@{budget}%")
+    _check_step(w, t, _host(t), layer, budget, n_rows=256, tag=f"cfg1@{budget}%")
 
 
 @pytest.mark.parametrize("fused", [False, True])
@@ -108,7 +146,8 @@ def test_config2_480p(fused):
     w = synth.WORKLOADS["cfg2"]
     t = synth.make_layer_inputs(w, seed=0, device=DEV)
     layer = LayerStep(w.N, w.H, w.D, w.torch_dtype, device=DEV, fused_update=fused)
-    _check_step(w, t, _host(t), layer, 40, n_rows=48, tag="cfg2" + ("/fused" if fused else ""))
+    _check_step(w, t, _host(t), layer, 40, n_rows=256, tag="cfg2" + ("/fused" if fused else ""),
+                reuse_key=("cfg2", 0, 40))
 
 
 @pytest.mark.parametrize("fused", [False, True])
@@ -116,7 +155,8 @@ def test_config3_720p_headline(fused):
     w = synth.WORKLOADS["cfg3"]
     t = synth.make_layer_inputs(w, seed=0, device=DEV)
     layer = LayerStep(w.N, w.H, w.D, w.torch_dtype, device=DEV, fused_update=fused)
-    _check_step(w, t, _host(t), layer, 30, n_rows=24, tag="cfg3" + ("/fused" if fused else ""))
+    _check_step(w, t, _host(t), layer, 30, n_rows=256, tag="cfg3" + ("/fused" if fused else ""),
+                reuse_key=("cfg3", 0, 30))
 
 
 @pytest.mark.parametrize("budget", [10, 100])
@@ -126,30 +166,63 @@ def test_config3_at_the_ends_of_the_budget_range(budget):
     w = synth.WORKLOADS["cfg3"]
     t = synth.make_layer_inputs(w, seed=0, device=DEV)
     layer = LayerStep(w.N, w.H, w.D, w.torch_dtype, device=DEV)
-    _check_step(w, t, _host(t), layer, budget, n_rows=16, tag=f"cfg3@{budget}%")
+    _check_step(w, t, _host(t), layer, budget, n_rows=256, tag=f"cfg3@{budget}%")
 
 
-def test_config4_sweep_three_steps_with_carried_caches():
-    """Budgets from the drawn schedule, fresh features / Q / K / V rows per step, caches carried over."""
+def _first_visit_order(schedule):
+    """The budget levels in the order the drawn schedule first reaches them."""
+    seen = []
+    for pct in schedule:
+        if pct not in seen:
+            seen.append(pct)
+    return seen
+
+
+CFG4_LEVELS = _first_visit_order(synth.budget_schedule(0, 50))
+
+
+class _Sweep:
+    """State of the config-4 run carried from one parametrised case to the next: the layer, the device tensors,
+    their host copies as the oracle sees them, and which cached output rows are still the seeded draw."""
+    layer = None
+    t = None
+    host = None
+    never_selected = None
+    step = 0
+
+
+@pytest.mark.parametrize("budget", CFG4_LEVELS)
+def test_config4_every_budget_level_with_carried_caches(budget):
+    """Config 4 at full size: one step per budget level 10 %, 20 %, ..., 100 % (in the order the drawn 50-step
+    schedule first reaches them), fresh features / Q / K / V rows per step, the K/V and output caches carried
+    from step to step on both sides.  Every level has its own launch plan (items per XCD, how many are cut
+    into key ranges, how many ranges), so every level is checked: scores, indices, K/V caches and untouched
+    rows in full and bit for bit, the attention on 64 sampled rows including rows of cut work items."""
     w = synth.WORKLOADS["cfg4"]
-    sched = synth.budget_schedule(0, 50)[:3]
-    layer = LayerStep(w.N, w.H, w.D, w.torch_dtype, device=DEV)
-    t = synth.make_layer_inputs(w, seed=0, device=DEV, step=0)
-    host = _host(t)
-    never_selected = np.ones(w.N, dtype=bool)       # rows whose cached output is still the seeded draw
-    for s, pct in enumerate(sched):
-        if s > 0:
-            fresh = synth.make_layer_inputs(w, seed=0, device=DEV, step=s)
-            for name in ("x_prev", "x_cur", "q", "k_new", "v_new"):
-                t[name] = fresh[name]
-                host[name] = to_np(fresh[name])
-            del fresh
-        kc, vc, e_idx = _check_step(w, t, host, layer, pct, n_rows=8, tag=f"cfg4 step {s} ({pct}%)",
-                                    out_known=never_selected)
-        # carry the oracle's own K/V caches; output rows selected once are no longer known to the oracle
-        # in full (it recomputes samples only), so later steps compare them as "must not move" only
-        host["k_cache"], host["v_cache"] = kc.reshape(w.N, w.H, w.D), vc.reshape(w.N, w.H, w.D)
-        never_selected[e_idx] = False
+    assert sorted(CFG4_LEVELS) == list(range(10, 101, 10))
+    sw = _Sweep
+    if sw.layer is None:
+        sw.layer = LayerStep(w.N, w.H, w.D, w.torch_dtype, device=DEV)
+        sw.t = synth.make_layer_inputs(w, seed=0, device=DEV, step=0)
+        sw.host = _host(sw.t)
+        sw.never_selected = np.ones(w.N, dtype=bool)      # rows whose cached output is still the seeded draw
+    else:
+        fresh = synth.make_layer_inputs(w, seed=0, device=DEV, step=sw.step)
+        for name in ("x_prev", "x_cur", "q", "k_new", "v_new"):
+            sw.t[name] = fresh[name]
+            sw.host[name] = to_np(fresh[name])
+        del fresh
+    kc, vc, e_idx = _check_step(w, sw.t, sw.host, sw.layer, budget, n_rows=64,
+                                tag=f"cfg4 step {sw.step} ({budget}%)", out_known=sw.never_selected)
+    # carry the oracle's own K/V caches; output rows selected once are no longer known to the oracle
+    # in full (it recomputes samples only), so later steps compare them as "must not move" only
+    sw.host["k_cache"], sw.host["v_cache"] = kc.reshape(w.N, w.H, w.D), vc.reshape(w.N, w.H, w.D)
+    sw.never_selected[e_idx] = False
+    sw.step += 1
+    if sw.step == len(CFG4_LEVELS):                       # release 12 GB of device and host memory
+        sw.layer = sw.t = sw.host = sw.never_selected = None
+        sw.step = 0
+        torch.cuda.empty_cache()
 
 
 def test_budget_zero_and_full():

@@ -2,7 +2,7 @@
 
 Bars: selected indices, masks, counters and moved rows bit-exact; scores bit-exact (the score
 decides integers, both sides take it in fp32 with the same channel order); attention max-abs
-<= 1e-4 in fp32 mode and relative L2 <= 1e-2 in bf16 mode.
+<= 1e-4 in fp32 mode and relative L2 <= 1e-2 in bf16 mode, over the whole comparison and over every (row, head) by itself.
 """
 import math
 
@@ -11,7 +11,7 @@ import pytest
 import torch
 
 import oracle
-from conftest import bf16_bits_to_f64, to_np
+from conftest import assert_rel_l2, bf16_bits_to_f64, to_np
 from paper_2506_05096_amd import binding as ab
 from paper_2506_05096_amd import synth
 
@@ -122,6 +122,23 @@ def test_topk_bit_exact(kind, n):
         assert np.array_equal(skip, oracle.update_skip_count(skip0, e_mask)), (kind, n, k)
 
 
+@pytest.mark.parametrize("kind", ["tied", "narrow", "lognormal"])
+@pytest.mark.parametrize("n", [32767, 32768, 32769, 32768 + 2048])
+def test_topk_on_both_sides_of_the_single_workgroup_limit(kind, n):
+    """Up to 32768 scores are selected by one workgroup with the keys in LDS, more by the multi-launch path:
+    the two must agree with the oracle right at the switch, with heavily tied and narrow-band scores (whose
+    threshold value is shared by many elements, so that the lowest-index rule decides) and at the budgets'
+    ends."""
+    s = synth.random_scores(n, 11 + n, kind)
+    for k in (0, 1, n // 10, (3 * n) // 10, n // 2, n - 1, n):
+        e_idx, e_rem, e_mask = oracle.topk(s.numpy(), k)
+        idx, rem, mask, skip0, skip = _run_topk(s, k)
+        assert np.array_equal(idx, e_idx), (kind, n, k)
+        assert np.array_equal(rem, e_rem), (kind, n, k)
+        assert np.array_equal(mask, e_mask), (kind, n, k)
+        assert np.array_equal(skip, oracle.update_skip_count(skip0, e_mask)), (kind, n, k)
+
+
 def test_topk_special_values():
     s = torch.tensor([float("nan"), -0.0, 0.0, float("inf"), -float("inf"), 1.0, float("nan"), 0.0, -1e-45, 1e-45,
                       3.4e38, -3.4e38])
@@ -218,10 +235,6 @@ def test_attn_f32_matches_oracle(n, h, d, k_sel):
         assert np.max(np.abs(lse - else_)) <= 1e-4
 
 
-def _rel_l2(a, b):
-    return float(np.linalg.norm((a - b).ravel()) / np.linalg.norm(b.ravel()))
-
-
 @pytest.mark.parametrize("n,h,k_sel,bias", [(1000, 3, 333, 0.0), (64, 1, 64, 0.0), (129, 2, 1, 0.0),
                                             (2500, 2, 130, 0.5), (4096, 2, 128, 0.0),
                                             (1, 1, 1, 0.0), (1, 24, 1, 0.0), (63, 2, 63, 0.0), (191, 1, 7, 0.0)])
@@ -232,8 +245,7 @@ def test_attn_bf16_matches_oracle(n, h, k_sel, bias):
     eo, else_ = oracle.sparse_attn(to_np(q), to_np(k), to_np(v), idx.numpy(), scale)
     for compact in (False, True):
         o, lse = _run_attn(q, k, v, idx, scale, compact=compact)
-        assert np.all(np.isfinite(o))
-        assert _rel_l2(o, eo) <= 1e-2, _rel_l2(o, eo)
+        assert_rel_l2(o, eo, tag=f"bf16 attention n={n} h={h} k_sel={k_sel} compact={compact}")
         assert np.max(np.abs(lse - else_)) <= 2e-2
 
 
@@ -285,8 +297,8 @@ def test_attn_bf16_logits_that_outgrow_the_first_tile(shape):
     scale = 1.0 / math.sqrt(d)
     eo, else_ = oracle.sparse_attn(to_np(q), to_np(k), to_np(v), idx.numpy(), scale)
     o, lse = _run_attn(q, k, v, idx, scale)
-    assert np.all(np.isfinite(o)) and np.all(np.isfinite(lse))
-    assert _rel_l2(o, eo) <= 1e-2, _rel_l2(o, eo)
+    assert np.all(np.isfinite(lse))
+    assert_rel_l2(o, eo, tag=shape)
     # lse is 50 to 280 here and the logits behind it reach 400 in the log2 units the kernel works in, where
     # one fp32 ulp is 3e-5: a handful of roundings at that size
     assert np.max(np.abs(lse - else_) / np.maximum(1.0, np.abs(else_))) <= 3e-5
@@ -308,8 +320,7 @@ def test_attn_bf16_split_items_match_oracle(n, h, k_sel):
     scale = 1.0 / math.sqrt(d)
     eo, else_ = oracle.sparse_attn(to_np(q), to_np(k), to_np(v), idx.numpy(), scale)
     o, lse = _run_attn(q, k, v, idx, scale)
-    assert np.all(np.isfinite(o))
-    assert _rel_l2(o, eo) <= 1e-2, _rel_l2(o, eo)
+    assert_rel_l2(o, eo, tag=f"split items n={n} h={h} k_sel={k_sel}")
     assert np.max(np.abs(lse - else_)) <= 2e-2
     # determinism: the same call twice gives the same bits
     o2, _ = _run_attn(q, k, v, idx, scale)
@@ -341,7 +352,10 @@ def test_attention_accepts_head_major_and_packed_layouts(dtype, d):
     assert np.array_equal(run(packed[:, 0], packed[:, 1], packed[:, 2]), base)
     eo, _ = oracle.sparse_attn(to_np(q), to_np(k), to_np(v), idx.numpy(), scale)
     got = as_f64(base)
-    assert (np.max(np.abs(got - eo)) <= 1e-4) if dtype == torch.float32 else (_rel_l2(got, eo) <= 1e-2)
+    if dtype == torch.float32:
+        assert np.max(np.abs(got - eo)) <= 1e-4
+    else:
+        assert_rel_l2(got, eo, tag="layouts")
 
 
 @pytest.mark.parametrize("dtype,d,n_ctx,k_sel", [(torch.bfloat16, 128, 77, 1000), (torch.bfloat16, 128, 256, 5000),
@@ -368,7 +382,7 @@ def test_cross_attention_of_selected_rows(dtype, d, n_ctx, k_sel):
     if dtype == torch.float32:
         assert np.max(np.abs(got - eo)) <= 1e-4
     else:
-        assert _rel_l2(got, eo) <= 1e-2
+        assert_rel_l2(got, eo, tag="cross-attention")
     # the bf16 kernel sums the bf16-rounded probabilities (the values its second product uses): few keys, little averaging
     assert np.max(np.abs(lse.cpu().numpy() - else_)) <= (1e-4 if dtype == torch.float32 else 1e-3)
 
@@ -412,7 +426,7 @@ def test_attn_update_equals_attention_then_scatter(dtype, n, h, d, k_sel, pad):
     if dtype == torch.float32:
         assert np.max(np.abs(got - eo)) <= 1e-4
     else:
-        assert _rel_l2(got, eo) <= 1e-2
+        assert_rel_l2(got, eo, tag="attention fused with the cache update")
 
 
 # ------------------------------------------------------------ kernel timer --
@@ -527,3 +541,25 @@ def test_attn_f32_key_range_shares_match_oracle_and_the_unsplit_run(n, h, d, k_s
     assert np.max(np.abs(got[idx.numpy()][:, :h * d].reshape(k_sel, h, d) - eo)) <= 1e-4
     rest = np.setdiff1d(np.arange(n), idx.numpy())
     assert np.array_equal(got[rest], cache0.numpy()[rest]) and np.array_equal(got[:, h * d:], cache0.numpy()[:, h * d:])
+
+
+def test_attn_f32_layer_workspace_sized_once_serves_the_small_budgets():
+    """A layer sizes its attention workspace once, for the largest selection.  The fp32 path cuts small
+    selections into more key ranges than large ones, so that size must cover them: at N = 8192, H = 8 the
+    full selection is not cut at all, yet at a 25 % budget the cut must be in use (its partial results land
+    in the workspace) and the rows must meet the fp32 bar."""
+    from paper_2506_05096_amd.layer import LayerStep
+    n, h, d = 8192, 8, 64
+    layer = LayerStep(n, h, d, torch.float32, device=DEV)
+    assert layer.attn_ws is not None and layer.attn_ws.numel() >= ab.workspace_bytes(ab.OP_SPARSE_ATTN, n, n // 4, h, d) > 0
+    q, k, v, idx = _attn_case(n, h, d, n // 4, torch.float32, seed=91)
+    t = {"q": q.to(DEV), "k_cache": k.to(DEV), "v_cache": v.to(DEV)}
+    layer.idx_sel[:n // 4].copy_(idx.to(DEV))
+    layer.attn_ws.fill_(0xAB)
+    layer.step_attn(t, n // 4)
+    _sync()
+    assert int((layer.attn_ws != 0xAB).sum().item()) > 0, "the key-range split did not run: no partial results were written"
+    rows = np.unique(np.concatenate([[0, 1, n // 4 - 1], np.random.default_rng(3).integers(0, n // 4, 61)]))
+    eo, _ = oracle.sparse_attn(to_np(q), to_np(k), to_np(v), idx.numpy()[rows], 1.0 / math.sqrt(d))
+    got = layer.o_sel[:n // 4].cpu().numpy().astype(np.float64)[rows]
+    assert np.max(np.abs(got - eo)) <= 1e-4

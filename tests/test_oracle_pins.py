@@ -354,6 +354,16 @@ def test_lse_weight_closed_forms_and_library():
     w2 = np.zeros(40, np.float32)
     oracle.lse_weight_update(w2, lse2, sel)
     assert np.allclose(w2[sel], ref, rtol=1e-6)
+    # saturation: a head's mean exponential is capped at e^64, so logits beyond fp32's exponential range give a
+    # large finite weight instead of inf (closed forms: all heads capped -> e^64; one of three capped -> e^64 / 3
+    # plus the two ordinary heads; the cap applies to lse - ln N, so lse = 64 + ln N is exactly at it)
+    w3 = np.zeros(n, np.float32)
+    lse3 = np.array([[1000.0, 500.0, 89.0], [math.log(n), 300.0, math.log(n)],
+                     [64.0 + math.log(n)] * 3, [64.0, 64.0, 64.0]])
+    oracle.lse_weight_update(w3, lse3, np.array([1, 2, 3, 5], np.int32))
+    e64 = math.exp(64.0)
+    assert np.all(np.isfinite(w3))
+    assert np.allclose(w3[[1, 2, 3, 5]], [e64, (e64 + 2.0) / 3.0, e64, e64 / n], rtol=1e-6)
 
 
 # ------------------------------------------------------- scatter / gather --
