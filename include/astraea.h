@@ -105,6 +105,22 @@ int astraea_select_topk(const float *score, int64_t N, int64_t k, int32_t *idx_s
                         void *stream);
 
 /*
+ * astraea_select_topk_static - astraea_select_topk for callers that cannot allocate device memory or
+ * hand over a workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments without the workspace, same result to the bit.  The selection state, the
+ * digit histogram and the per-workgroup counts live in a device array built into the library
+ * (24.25 KiB per GPU, held until the process ends); the call allocates and frees nothing.
+ *   N           at most 4194304 (2^22) scores; more returns ASTRAEA_ERR_UNSUPPORTED and enqueues nothing.
+ * The GPU that `stream` belongs to must be the current device.  The array's address on that device is
+ * looked up at the first call made with it current (hipGetSymbolAddress; make that first call outside
+ * a graph capture).  All calls on one GPU share the one array, whatever their stream: two calls
+ * that overlap in time on the same GPU race, so order them on one stream or with events.  Every
+ * call clears what it needs at its start, with a kernel, so calls of any sizes may follow each other.
+ */
+int astraea_select_topk_static(const float *score, int64_t N, int64_t k, int32_t *idx_sel, int32_t *idx_remain,
+                               uint8_t *sel_mask, int32_t *skip_count, void *stream);
+
+/*
  * astraea_sparse_attn_fwd - attention of the selected queries over the full-length
  * keys and values (Algorithm 1 step 6; Sec. 3.2 "Sparse Attention"):
  *     o_sel[r, h, :] = sum_j softmax_j(scale * <q_r,h , k_j,h>) * v_j,h      j = 0..N-1

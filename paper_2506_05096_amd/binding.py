@@ -25,7 +25,7 @@ ACT_NONE, ACT_GELU_TANH = 0, 1
 CROSSOVER_UNIFORM, CROSSOVER_BLOCK = 0, 1
 
 EXPORTS = (
-    "astraea_score", "astraea_select_topk", "astraea_sparse_attn_fwd", "astraea_sparse_attn_update_fwd",
+    "astraea_score", "astraea_select_topk", "astraea_select_topk_static", "astraea_sparse_attn_fwd", "astraea_sparse_attn_update_fwd",
     "astraea_scatter_update", "astraea_gather_rows", "astraea_sparse_linear", "astraea_workspace_bytes", "astraea_budget_to_k", "astraea_attn_flops",
     "astraea_probe_mfma_bf16", "astraea_probe_copy", "astraea_probe_kernel_timer", "astraea_probe_kernel_count",
     "astraea_probe_kernel_ms", "astraea_lse_weight_update", "astraea_attn_plan", "astraea_check_indices",
@@ -64,6 +64,8 @@ def lib() -> C.CDLL:
         vp, i64, i32, f32, sz = C.c_void_p, C.c_int64, C.c_int32, C.c_float, C.c_size_t
         L.astraea_score.argtypes = [vp, vp, C.c_int, i64, i64, i64, C.c_int, vp, vp, vp, i32, f32, f32, vp, vp]
         L.astraea_select_topk.argtypes = [vp, i64, i64, vp, vp, vp, vp, vp, sz, vp]
+        L.astraea_select_topk_static.argtypes = [vp, i64, i64, vp, vp, vp, vp, vp]
+        L.astraea_select_topk_static.restype = C.c_int
         L.astraea_sparse_attn_fwd.argtypes = [vp, vp, vp, C.c_int, i64, i32, i32, i64, i64, i64, i64, vp, i64,
                                               C.c_int, f32, vp, vp, vp, sz, vp]
         L.astraea_sparse_attn_update_fwd.argtypes = [vp, vp, vp, C.c_int, i64, i32, i32, i64, i64, i64, i64, vp, i64,
@@ -163,6 +165,14 @@ def astraea_select_topk(score: torch.Tensor, k: int, idx_sel: torch.Tensor, work
     _check(lib().astraea_select_topk(_p(score), score.numel(), k, _p(idx_sel), _p(idx_remain), _p(sel_mask),
                                      _p(skip_count), _p(workspace), workspace.numel() * workspace.element_size(),
                                      _stream()))
+
+
+def astraea_select_topk_static(score: torch.Tensor, k: int, idx_sel: torch.Tensor,
+                               idx_remain: Optional[torch.Tensor] = None, sel_mask: Optional[torch.Tensor] = None,
+                               skip_count: Optional[torch.Tensor] = None) -> None:
+    assert score.dtype == torch.float32 and score.is_contiguous() and idx_sel.dtype == torch.int32
+    _check(lib().astraea_select_topk_static(_p(score), score.numel(), k, _p(idx_sel), _p(idx_remain), _p(sel_mask),
+                                            _p(skip_count), _stream()))
 
 
 def astraea_sparse_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, idx_sel: Optional[torch.Tensor],

@@ -58,24 +58,45 @@ int astraea_score(const void *x_cur, const void *x_prev, astraea_dtype dt, int64
                         table_len, w_alpha, w_beta, score_out, (hipStream_t)stream);
 }
 
+static int check_topk(const char *fn, const float *score, int64_t N, int64_t k, const int32_t *idx_sel,
+                      const int32_t *idx_remain, const int32_t *skip_count)
+{
+    if (N < 0 || N > kMaxTokens) return fail(ASTRAEA_ERR_INVALID, "%s: N=%lld out of range", fn, (long long)N);
+    if (k < 0 || k > N) return fail(ASTRAEA_ERR_INVALID, "%s: k=%lld not in [0, N=%lld]", fn, (long long)k, (long long)N);
+    if (N == 0) return ASTRAEA_OK;
+    if (!score) return fail(ASTRAEA_ERR_INVALID, "%s: NULL score", fn);
+    if (k > 0 && !idx_sel) return fail(ASTRAEA_ERR_INVALID, "%s: NULL idx_sel", fn);
+    if (((uintptr_t)score | (uintptr_t)idx_sel | (uintptr_t)idx_remain | (uintptr_t)skip_count) % 4 != 0)
+        return fail(ASTRAEA_ERR_INVALID, "%s: pointer not 4-byte aligned", fn);
+    return ASTRAEA_OK;
+}
+
 int astraea_select_topk(const float *score, int64_t N, int64_t k, int32_t *idx_sel, int32_t *idx_remain,
                         uint8_t *sel_mask, int32_t *skip_count, void *workspace, size_t workspace_bytes,
                         void *stream)
 {
-    if (N < 0 || N > kMaxTokens)
-        return fail(ASTRAEA_ERR_INVALID, "astraea_select_topk: N=%lld out of range", (long long)N);
-    if (k < 0 || k > N)
-        return fail(ASTRAEA_ERR_INVALID, "astraea_select_topk: k=%lld not in [0, N=%lld]", (long long)k, (long long)N);
-    if (N == 0) return ASTRAEA_OK;
-    if (!score) return fail(ASTRAEA_ERR_INVALID, "astraea_select_topk: NULL score");
-    if (k > 0 && !idx_sel) return fail(ASTRAEA_ERR_INVALID, "astraea_select_topk: NULL idx_sel");
-    if (((uintptr_t)score | (uintptr_t)idx_sel | (uintptr_t)idx_remain | (uintptr_t)skip_count) % 4 != 0)
-        return fail(ASTRAEA_ERR_INVALID, "astraea_select_topk: pointer not 4-byte aligned");
+    const int rc = check_topk("astraea_select_topk", score, N, k, idx_sel, idx_remain, skip_count);
+    if (rc != ASTRAEA_OK || N == 0) return rc;
     const size_t need = topk_workspace_bytes(N);
     if (!workspace || (uintptr_t)workspace % 256 != 0 || workspace_bytes < need)
         return fail(ASTRAEA_ERR_WORKSPACE, "astraea_select_topk: workspace must be 256-byte aligned and >= %zu bytes",
                     need);
     return launch_select_topk(score, N, k, idx_sel, idx_remain, sel_mask, skip_count, workspace, (hipStream_t)stream);
+}
+
+int astraea_select_topk_static(const float *score, int64_t N, int64_t k, int32_t *idx_sel, int32_t *idx_remain,
+                               uint8_t *sel_mask, int32_t *skip_count, void *stream)
+{
+    const int rc = check_topk("astraea_select_topk_static", score, N, k, idx_sel, idx_remain, skip_count);
+    if (rc != ASTRAEA_OK || N == 0) return rc;
+    if (N > topk_static_max_n())
+        return fail(ASTRAEA_ERR_UNSUPPORTED,
+                    "astraea_select_topk_static: N=%lld exceeds the %lld scores the built-in scratch array holds; use "
+                    "astraea_select_topk with a workspace", (long long)N, (long long)topk_static_max_n());
+    void *scratch_ptr = nullptr;
+    const int rs = topk_static_scratch(&scratch_ptr);
+    if (rs != ASTRAEA_OK) return rs;
+    return launch_select_topk(score, N, k, idx_sel, idx_remain, sel_mask, skip_count, scratch_ptr, (hipStream_t)stream);
 }
 
 // Shared body of the two attention entry points: `out` is either the compact [k_sel, H, D] result

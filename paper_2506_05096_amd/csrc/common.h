@@ -27,6 +27,8 @@ int launch_score(const void *x_cur, const void *x_prev, astraea_dtype dt, int64_
                  hipStream_t stream);
 
 size_t topk_workspace_bytes(int64_t N);
+int64_t topk_static_max_n();
+int topk_static_scratch(void **ptr_out);      // the library's own per-device scratch array, for astraea_select_topk_static
 int launch_select_topk(const float *score, int64_t N, int64_t k, int32_t *idx_sel, int32_t *idx_remain,
                        uint8_t *sel_mask, int32_t *skip_count, void *workspace, hipStream_t stream);
 

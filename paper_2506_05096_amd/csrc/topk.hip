@@ -13,6 +13,8 @@
 //      precede it.  Ranks come from wavefront ballots and prefix popcounts.
 // The score array (4N bytes) stays in L2 across the five small launches; the step is latency-bound.
 // Up to 32768 scores take a single-workgroup kernel instead (one launch, keys held in LDS).
+#include <mutex>
+
 #include "common.h"
 
 namespace astraea {
@@ -410,7 +412,44 @@ __global__ __launch_bounds__(kSmallThreads) void topk_small_kernel(const float *
     }
 }
 
+// ---- astraea_select_topk_static: the same selection for callers that cannot allocate.  The selection state,
+// the histogram and the per-workgroup counts live in this file-scope device array instead of a caller's
+// workspace: 256 B of state + 8 KiB of histogram + 8 B per 2048 scores, 24.25 KiB for the largest input
+// the entry point takes.  Every GPU the library runs on holds its own copy, at its own address, until the
+// process ends.  In host code the array's name only stands for the symbol: the address kernels are given is
+// the one hipGetSymbolAddress returns for the device that is current, looked up once per device.
+constexpr int64_t kStaticMaxN = (int64_t)1 << 22;
+constexpr size_t kStaticBytes = sizeof(SelectState) + kBins * sizeof(uint32_t) + 2 * (size_t)(kStaticMaxN / kChunk) * sizeof(uint32_t);
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+void *g_scratch_ptr[kMaxDevices] = {};
+
 }  // namespace
+
+int64_t topk_static_max_n() { return kStaticMaxN; }
+
+// Device address of `scratch` on the current device (first use on a device looks it up and keeps it).
+int topk_static_scratch(void **ptr_out)
+{
+    static_assert(kStaticBytes % 256 == 0, "scratch size keeps the 256-byte granularity of the workspace");
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(ASTRAEA_ERR_HIP, "astraea_select_topk_static: hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices)
+        return fail(ASTRAEA_ERR_UNSUPPORTED, "astraea_select_topk_static: device ordinal %d not below %d", dev, kMaxDevices);
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return fail(ASTRAEA_ERR_HIP, "astraea_select_topk_static: hipGetSymbolAddress: %s", hipGetErrorString(e));
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr_out = g_scratch_ptr[dev];
+    return ASTRAEA_OK;
+}
 
 size_t topk_workspace_bytes(int64_t N)
 {
