@@ -136,12 +136,18 @@ int astraea_select_topk_static(const float *score, int64_t N, int64_t k, int32_t
  *   workspace   at least astraea_workspace_bytes(ASTRAEA_OP_SPARSE_ATTN, N, k_sel, H, D) bytes,
  *               256-byte aligned (may be NULL when that is 0).  The bf16 path stages a re-tiled
  *               copy of V there (N rounded up to 64, times H*D*2 bytes) plus 68 MB of partial
- *               results on every call; contents need not be initialised and are clobbered.
+ *               results and 4 bytes per workgroup of the largest launch (flags of the workgroups
+ *               a second launch redoes, see below) on every call; contents need not be
+ *               initialised and are clobbered.
  *               The fp32 path uses it only for a selection too small to fill the chip, which
  *               it then cuts into key ranges (up to 8 x k_sel x H x (D + 4) floats of partial
  *               results); there the workspace is optional: with NULL, or fewer bytes than
  *               named, every work item sweeps all keys itself and the result is the same up
  *               to summation order.
+ * The bf16 path runs its main kernel with each row's exponent offset fixed at the row max over the
+ * first key tile, which is exact as long as no later logit exceeds that max by more than 80 powers of
+ * two; workgroups with a row that does are redone by a second launch that takes a max per key tile.
+ * The result does not depend on which of the two served a row beyond rounding.
  * Supported: (BF16, D = 128) on bf16 MFMA with fp32 softmax and accumulation;
  * (F32, D = 64 or 128) on fp32 MFMA.  k_sel == 0 enqueues nothing.
  * Pointers must be 16-byte aligned and strides multiples of 8 elements.
@@ -332,8 +338,8 @@ int astraea_probe_copy(const void *src, void *dst, int64_t bytes, void *stream);
 /*
  * Kernel timer, also a measurement aid.  astraea_probe_kernel_timer(1) makes every following
  * astraea_sparse_attn_fwd / astraea_sparse_attn_update_fwd call of this thread record a pair of HIP
- * events on its stream around its main kernel alone (not the V re-tiling pre-pass, not the merge of
- * partial results), for up to 64 calls; (0) stops it; either resets the count.  The events are created
+ * events on its stream around its main kernel alone (not the V re-tiling pre-pass, not the launch that
+ * redoes flagged workgroups, not the merge of partial results), for up to 64 calls; (0) stops it; either resets the count.  The events are created
  * on the first enable and kept.  astraea_probe_kernel_count returns how many launches were timed,
  * astraea_probe_kernel_ms(i, &ms) waits for launch i to finish and returns its duration (host pointer).
  */

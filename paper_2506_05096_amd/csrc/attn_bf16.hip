@@ -23,8 +23,13 @@
 //    2*N*H*D*2 bytes, under 1% of the attention time, and needs N_pad*H*D*2 bytes of workspace.
 //  * queries are gathered by index while loading the Q fragment, which then lives in registers
 //    for the whole sweep (the "gather" step of the path is fused here).
-//  * the rescale of the O accumulators is lazy: the running max is only raised when some row's
-//    max grew by more than 2^kTau, so stale maxima cost range, not accuracy.
+//  * the exponent offset of a row need not be its exact max: a stale one costs range, not accuracy
+//    (P, the row sums and the O accumulators are floating point with 8-bit exponents).  The main
+//    kernel therefore fixes each row's offset at the max over the first key tile and takes no max in
+//    the sweep at all, which removes a fifth of the softmax arithmetic.  A row whose later logits
+//    outgrow that offset by more than 2^80 (or overflow) shows in its final row sum; its workgroup
+//    then flags itself, writes nothing, and a second launch of the same kernel in its exact form
+//    (a max per tile, lazy rescale when it grew by more than 2^kTau) redoes just the flagged ones.
 //  * workgroup ids are mapped so that the workgroups resident on one XCD work on the same head and
 //    sweep the keys together; K/V tiles are then served from that XCD's L2.
 //  * the two waves that share a SIMD alternate: while one runs the MFMAs of a tile the other runs
@@ -44,7 +49,8 @@ constexpr int kBk = 64;                 // keys per LDS tile
 constexpr int kRowBytes = D * 2;        // 256 B per key row, unpadded
 constexpr int kTileBytes = kBk * kRowBytes;          // 16 KiB
 constexpr int kBufBytes = 2 * kTileBytes;            // K tile then V tile
-constexpr float kTau = 8.0f;            // lazy-rescale threshold, log2 units
+constexpr float kTau = 8.0f;            // exact form: lazy-rescale threshold, log2 units
+constexpr float kBig = 0x1p80f;         // fast form: a final row sum above this sends the workgroup to the exact form
 constexpr int kNumXcd = 8;
 
 __device__ __forceinline__ float xhalf_max(float x)
@@ -133,15 +139,22 @@ constexpr int MFMA = 0x008, DSR = 0x100;
         __builtin_amdgcn_sched_barrier(0); \
     } while (0)
 
+// EXACT = false: the main launch (offset fixed by the first tile, no max in the sweep); every workgroup
+// writes redo[blockIdx.x] = 1 if one of its rows outgrew the offset (and then stores no result), else 0.
+// EXACT = true: the second launch over the same grid; a workgroup whose flag is 0 returns at once, the
+// others sweep their keys again with a max per tile and store their results.
+template <bool EXACT>
 __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
     const __bf16 *__restrict__ q, const __bf16 *__restrict__ k, const char *__restrict__ vt, int64_t N, int32_t H,
     int64_t q_stride_n, int64_t q_stride_h, int64_t kv_stride_n, int64_t kv_stride_h,
     const int32_t *__restrict__ idx_sel, int64_t k_sel, int q_is_compact, float scale_log2e,
     __bf16 *__restrict__ o_sel, int64_t o_stride_n, int o_scatter, float *__restrict__ lse_sel, AttnSchedule sch,
-    float *__restrict__ partial)
+    float *__restrict__ partial, uint32_t *__restrict__ redo)
 {
     // [parity][K tile | V^T tile]; 64 KiB, one 8-wave workgroup per CU (two waves per SIMD)
     __shared__ __attribute__((aligned(1024))) char lds[2 * kBufBytes];
+    __shared__ uint32_t wave_outgrew[kWaves];
+    if (EXACT && redo && redo[blockIdx.x] == 0) return;     // no flag array: the exact form runs alone
 
     const int64_t ntiles = (N + kBk - 1) / kBk;
     const int64_t total_items = (int64_t)H * sch.q_tiles;
@@ -223,8 +236,9 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
         }
     };
 
-    // ---- LDS read offsets (relative to the array) of the current parity; the parity bit is flipped in
-    // place every tile, and the array's base is added where the offsets are used
+    // ---- LDS read offsets relative to a buffer pair; the buffer parity and the array's base are added where
+    // the offsets are used (the tile loop is unrolled by two, so the parity is a compile-time constant there
+    // and lands in the read's immediate offset)
     // K fragment (kb, s): row 32*kb + qc, logical chunk 2*s + hf; kb is an immediate offset
     uint32_t ka[D / 16];
 #pragma unroll
@@ -238,10 +252,18 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
     floatx16 sacc[2];          // S^T of the current tile (two blocks of 32 keys)
     uint32_t pw[16];           // P^T as bf16 pairs: pw[8*kb + i] = registers 2i, 2i+1 of block kb
 
-    // VALU phase for tile j: row max, exponentials -> pw, row sums.  The running max is only raised
-    // (and what was accumulated under the old one rescaled) when some row's max moved up by more
-    // than 2^kTau; otherwise the stale max stays in use.
+    // VALU phase for tile j: exponentials -> pw, row sums; in the exact form first the row max: the running
+    // max is only raised (and what was accumulated under the old one rescaled) when some row's max moved up by
+    // more than 2^kTau, otherwise the stale max stays in use.
     // register i of sacc[kb]: key = 64*j + 32*kb + (i/4)*8 + hf*4 + i%4, query = qc
+    auto tile_row_max = [&]() __attribute__((always_inline)) -> float {
+        float tm = sacc[0][0];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) tm = fmaxf(tm, sacc[kb][i]);
+        return xhalf_max(tm) * scale_log2e;
+    };
     auto softmax_tile = [&](int64_t j) __attribute__((always_inline)) {
         if ((j + 1) * kBk > N) {                    // only the last tile can be ragged
 #pragma unroll
@@ -252,21 +274,18 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
                     if (key >= 0) sacc[kb][i] = -INFINITY;
                 }
         }
-        float tm = sacc[0][0];
+        if (EXACT) {
+            const float tmax = tile_row_max();
+            if (__builtin_amdgcn_ballot_w64(tmax > m_c + kTau) != 0) {
+                const float m_new = fmaxf(m_c, tmax);
+                const float alpha = __builtin_amdgcn_exp2f(m_c - m_new);   // 0 on the first tile
+                m_c = m_new;
+                l_run *= alpha;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+                for (int b = 0; b < 4; ++b)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) tm = fmaxf(tm, sacc[kb][i]);
-        const float tmax = xhalf_max(tm) * scale_log2e;
-        if (__builtin_amdgcn_ballot_w64(tmax > m_c + kTau) != 0) {
-            const float m_new = fmaxf(m_c, tmax);
-            const float alpha = __builtin_amdgcn_exp2f(m_c - m_new);   // 0 on the first tile
-            m_c = m_new;
-            l_run *= alpha;
-#pragma unroll
-            for (int b = 0; b < 4; ++b)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) oacc[b][i] *= alpha;
+                    for (int i = 0; i < 16; ++i) oacc[b][i] *= alpha;
+            }
         }
         float ps0 = 0.0f, ps1 = 0.0f;
         const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
@@ -293,11 +312,15 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
     // (lanes 0-31) and 16*tt + {4..7, 12..15} (lanes 32-63); V^T(j) is in the parity va[] points at.
     // Then, if WITH_QK, S^T = K Q^T for the tile in the parity ka[] points at: 16 MFMAs, two blocks
     // of 32 keys.  One LDS read pipeline runs through all 32 MFMAs.
-    auto mfma_phase = [&](auto qk_tag) __attribute__((always_inline)) {
+    // The buffer parity PAR of the phase is a compile-time constant: V^T(j) is read from buffer pair PAR, K(j+1)
+    // from pair PAR ^ 1.
+    auto mfma_phase = [&](auto qk_tag, auto par_tag) __attribute__((always_inline)) {
         constexpr bool WITH_QK = decltype(qk_tag)::value;
+        constexpr uint32_t VP = decltype(par_tag)::value * kBufBytes;
+        constexpr uint32_t KP = (decltype(par_tag)::value ^ 1) * kBufBytes;
         bf16x8 vf[16], kf[16];
 #pragma unroll
-        for (int u = 0; u < kAhead; ++u) vf[u] = lds_read_b128(lds0 + va[u >> 2] + (u & 3) * 32 * 128);
+        for (int u = 0; u < kAhead; ++u) vf[u] = lds_read_b128(lds0 + va[u >> 2] + (VP + (u & 3) * 32 * 128));
 #pragma unroll
         for (int u = 0; u < 16; ++u) {
             const int tt = u >> 2, b = u & 3;
@@ -305,9 +328,9 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
             oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[u], __builtin_bit_cast(bf16x8, p4), oacc[b], 0, 0, 0);
             const int n = u + kAhead;
             if (n < 16)
-                vf[n] = lds_read_b128(lds0 + va[n >> 2] + (n & 3) * 32 * 128);
+                vf[n] = lds_read_b128(lds0 + va[n >> 2] + (VP + (n & 3) * 32 * 128));
             else if (WITH_QK)
-                kf[n - 16] = lds_read_b128(lds0 + ka[(n - 16) & 7] + ((n - 16) >> 3) * 32 * kRowBytes);
+                kf[n - 16] = lds_read_b128(lds0 + ka[(n - 16) & 7] + (KP + ((n - 16) >> 3) * 32 * kRowBytes));
         }
         if (WITH_QK) {
 #pragma unroll
@@ -319,7 +342,7 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
             for (int u = 0; u < 16; ++u) {
                 sacc[u >> 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[u], qf[u & 7], sacc[u >> 3], 0, 0, 0);
                 const int n = u + kAhead;
-                if (n < 16) kf[n] = lds_read_b128(lds0 + ka[n & 7] + (n >> 3) * 32 * kRowBytes);
+                if (n < 16) kf[n] = lds_read_b128(lds0 + ka[n & 7] + (KP + (n >> 3) * 32 * kRowBytes));
             }
         }
         SGB(DSR, kAhead);
@@ -342,22 +365,6 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
             sacc[u >> 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                 lds_read_b128(lds0 + ka[u & 7] + (u >> 3) * 32 * kRowBytes), qf[u & 7], sacc[u >> 3], 0, 0, 0);
     };
-    // the asm pins keep the address updates where they are written (in a VALU phase)
-    auto flip_k = [&]() __attribute__((always_inline)) {
-#pragma unroll
-        for (int s = 0; s < D / 16; ++s) {
-            ka[s] ^= kBufBytes;
-            asm volatile("" : "+v"(ka[s]));
-        }
-    };
-    auto flip_v = [&]() __attribute__((always_inline)) {
-#pragma unroll
-        for (int tt = 0; tt < 4; ++tt) {
-            va[tt] ^= kBufBytes;
-            asm volatile("" : "+v"(va[tt]));
-        }
-    };
-
     // ---- ping-pong schedule.  K tile j lives in K buffer j & 1, V^T tile j in V buffer j & 1.
     // The 8 waves form two groups of 4 (one wave of each group per SIMD).  Each wave alternates a VALU
     // phase (exponentials of tile j) and an MFMA phase (second product of tile j, first product of
@@ -381,42 +388,65 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
     PHASE_BARRIER();
     if (grp == 1) PHASE_BARRIER();
     qk_mfmas();                    // S^T of the first tile (K buffer 0)
-    flip_k();                      // ka -> K buffer 1, where the second tile is
+    // fast form: the first tile's row max is the offset of the whole sweep (nothing is accumulated yet, so
+    // nothing needs rescaling; rows past the last key were filled with copies of it and cannot raise the max)
+    if (!EXACT) m_c = tile_row_max();
     PHASE_BARRIER();
 
-    for (int64_t j = tile_begin; j + 1 < tile_end; ++j) {
-        const int par = (int)((j - tile_begin) & 1);
-        // VALU phase of tile j
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    // One tile that has a successor: VALU phase of tile j, then the MFMA phase (second product of tile j from
+    // V buffer PAR, first product of tile j+1 from K buffer PAR ^ 1).
+    auto tile_step = [&](int64_t j, auto par_tag) __attribute__((always_inline)) {
+        constexpr int PAR = decltype(par_tag)::value;
         if (grp == 1) {
-            dma_v_tile(j + 1, par ^ 1, wig, W4{});
-            if (j + 2 < tile_end) dma_k_tile(j + 2, par, wig, W4{});
-        }
-        if (j > tile_begin) {      // buffers swap roles after every MFMA phase
-            flip_k();
-            flip_v();
+            dma_v_tile(j + 1, PAR ^ 1, wig, W4{});
+            if (j + 2 < tile_end) dma_k_tile(j + 2, PAR, wig, W4{});
         }
         softmax_tile(j);
         PHASE_BARRIER();
-        // MFMA phase: second product of tile j, first product of tile j+1.  The wave in this phase
-        // gets issue priority over its SIMD neighbour, which is in its VALU phase.
+        // The wave in its MFMA phase gets issue priority over its SIMD neighbour, which is in its VALU phase.
         __builtin_amdgcn_s_setprio(3);
-        mfma_phase(std::true_type{});
+        mfma_phase(std::true_type{}, par_tag);
         __builtin_amdgcn_s_setprio(0);
         if (grp == 1) wait_dma();
         PHASE_BARRIER();
-    }
+    };
     // last tile: no next tile to prefetch or to start
-    if (tile_end - tile_begin > 1) {
-        flip_k();
-        flip_v();
+    auto last_step = [&](int64_t j, auto par_tag) __attribute__((always_inline)) {
+        softmax_tile(j);
+        PHASE_BARRIER();
+        mfma_phase(std::false_type{}, par_tag);
+        PHASE_BARRIER();
+    };
+    // the loop is unrolled by two so that the buffer parity is a constant in each copy
+    int64_t j = tile_begin;
+    for (; j + 2 < tile_end; j += 2) {
+        tile_step(j, P0{});
+        tile_step(j + 1, P1{});
     }
-    softmax_tile(tile_end - 1);
-    PHASE_BARRIER();
-    mfma_phase(std::false_type{});
-    PHASE_BARRIER();
+    if (j + 1 < tile_end) {
+        tile_step(j, P0{});
+        last_step(j + 1, P1{});
+    } else {
+        last_step(j, P0{});
+    }
     if (grp == 0) PHASE_BARRIER();
 
     const float l_tot = xhalf_sum(l_run);
+    if (!EXACT) {
+        // Did a row outgrow its offset?  Its row sum then passed 2^80, or is infinite or NaN (the comparison is
+        // written so that those fail it too).  The workgroup decides as one: it stores either all of its rows or
+        // none and leaves them to the exact launch.
+        const bool outgrew = __builtin_amdgcn_ballot_w64(!(l_tot <= kBig)) != 0;
+        if (lane == 0) wave_outgrew[wave] = outgrew ? 1u : 0u;
+        __syncthreads();
+        uint32_t any = 0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) any |= wave_outgrew[w];
+        if (tid == 0) redo[blockIdx.x] = any;
+        if (any) return;
+    }
     if (pslot >= 0) {
         // a key-range share of an item: unnormalised accumulators, running max and row sum go to the
         // workspace; merge_partials_kernel combines the shares
@@ -556,16 +586,25 @@ int attn_bf16_plan(int64_t N, int32_t H, int64_t k_sel, int64_t plan[8])
 }
 
 // Workspace of the bf16 path: the V^T tiles written by the pre-pass, then the partial results of the
-// split items (at most kMaxSharesPerXcd shares per XCD).
+// split items (at most kMaxSharesPerXcd shares per XCD), then one redo flag per workgroup of the largest
+// grid a selection of up to N queries can launch.
 static size_t vt_bytes(int64_t N, int32_t H)
 {
     const int64_t ntiles = (N + kBk - 1) / kBk;
     return (size_t)ntiles * (size_t)H * kTileBytes;
 }
+static size_t partial_bytes() { return (size_t)kNumXcd * kMaxSharesPerXcd * kPartialFloats * sizeof(float); }
+// Workgroups of a launch: 8 * (full items + shares) per XCD <= all items rounded up to the XCD count, plus the shares.
+static size_t redo_flags(int64_t N, int32_t H)
+{
+    const int64_t items = ((N + kBq - 1) / kBq) * (int64_t)H;
+    return (size_t)(((items + kNumXcd - 1) / kNumXcd) * kNumXcd + (int64_t)kNumXcd * kMaxSharesPerXcd);
+}
 size_t attn_bf16_workspace_bytes(int64_t N, int32_t H)
 {
     if (N <= 0 || H <= 0) return 0;
-    return vt_bytes(N, H) + (size_t)kNumXcd * kMaxSharesPerXcd * kPartialFloats * sizeof(float);
+    const size_t b = vt_bytes(N, H) + partial_bytes() + redo_flags(N, H) * sizeof(uint32_t);
+    return (b + 255) & ~(size_t)255;
 }
 
 int launch_attn_bf16_d128(const void *q, const void *k, const void *v, int64_t N, int32_t H, int64_t q_stride_n,
@@ -586,15 +625,30 @@ int launch_attn_bf16_d128(const void *q, const void *k, const void *v, int64_t N
     const int64_t left = sch.items_per_xcd - sch.full_items;
     char *vt = (char *)workspace;
     float *partial = (float *)(vt + vt_bytes(N, H));
+    uint32_t *redo = (uint32_t *)((char *)partial + partial_bytes());
+    // compact queries may outnumber the keys (cross-attention of many rows over a short context): the flag
+    // area is sized for up to N queries, larger selections run the exact form alone, which needs no flags
+    const bool two_forms = (size_t)(slots * kNumXcd) <= redo_flags(N, H);
     hipLaunchKernelGGL(transpose_v_kernel, dim3((unsigned)ntiles, (unsigned)H), dim3(256), 0, stream,
                        (const __bf16 *)v, N, kv_stride_n, kv_stride_h, ntiles, vt);
     dim3 grid((unsigned)(slots * kNumXcd)), block(kWaves * kWave);
+    const float c = scale * 1.44269504088896340736f;
     kernel_timer_begin(stream);
-    hipLaunchKernelGGL(attn_bf16_kernel, grid, block, 0, stream, (const __bf16 *)q, (const __bf16 *)k,
-                       (const char *)vt, N, H, q_stride_n, q_stride_h, kv_stride_n, kv_stride_h, idx_sel, k_sel,
-                       q_is_compact, scale * 1.44269504088896340736f, (__bf16 *)o_sel, o_stride_n, o_scatter, lse_sel, sch,
-                       partial);
+    if (two_forms)
+        hipLaunchKernelGGL(attn_bf16_kernel<false>, grid, block, 0, stream, (const __bf16 *)q, (const __bf16 *)k,
+                           (const char *)vt, N, H, q_stride_n, q_stride_h, kv_stride_n, kv_stride_h, idx_sel, k_sel,
+                           q_is_compact, c, (__bf16 *)o_sel, o_stride_n, o_scatter, lse_sel, sch, partial, redo);
+    else
+        hipLaunchKernelGGL(attn_bf16_kernel<true>, grid, block, 0, stream, (const __bf16 *)q, (const __bf16 *)k,
+                           (const char *)vt, N, H, q_stride_n, q_stride_h, kv_stride_n, kv_stride_h, idx_sel, k_sel,
+                           q_is_compact, c, (__bf16 *)o_sel, o_stride_n, o_scatter, lse_sel, sch, partial,
+                           (uint32_t *)nullptr);
     kernel_timer_end(stream);
+    // the exact form over the same grid: only workgroups that flagged themselves do anything
+    if (two_forms)
+        hipLaunchKernelGGL(attn_bf16_kernel<true>, grid, block, 0, stream, (const __bf16 *)q, (const __bf16 *)k,
+                           (const char *)vt, N, H, q_stride_n, q_stride_h, kv_stride_n, kv_stride_h, idx_sel, k_sel,
+                           q_is_compact, c, (__bf16 *)o_sel, o_stride_n, o_scatter, lse_sel, sch, partial, redo);
     if (left > 0)
         hipLaunchKernelGGL(merge_partials_kernel, dim3((unsigned)(left * kNumXcd), kBq / 8), dim3(256), 0, stream, partial, sch,
                            H, k_sel, N, idx_sel, (__bf16 *)o_sel, o_stride_n, o_scatter, lse_sel);

@@ -304,6 +304,51 @@ def test_attn_bf16_logits_that_outgrow_the_first_tile(shape):
     assert np.max(np.abs(lse - else_) / np.maximum(1.0, np.abs(else_))) <= 3e-5
 
 
+@pytest.mark.parametrize("rise_nats", [20.0, 45.0])
+def test_attn_bf16_rows_that_outgrow_their_first_tile_by_a_tolerated_margin(rise_nats):
+    """The main launch fixes a row's exponent offset at the max over its first key tile; later logits may exceed
+    it by up to 2^80 before the row is handed to the exact form.  Here every logit past the first tile lies 20 or
+    45 nats (29 or 65 powers of two) above the first tile's, with a few single keys another 6 nats up: inside
+    the margin, so these rows are served with a stale offset, and must still meet the bar row by row."""
+    n, h, d = 1300, 2, 128
+    g = torch.Generator().manual_seed(23)
+    v = torch.randn(n, h, d, generator=g)
+    k = 0.05 * torch.randn(n, h, d, generator=g)
+    q = 0.05 * torch.randn(n, h, d, generator=g)
+    scale = 1.0 / math.sqrt(d)
+    q[:, :, 0] = 8.0
+    b = torch.full((n,), rise_nats / (8.0 * scale))
+    b[:64] = 0.0
+    b[[300, 777, 1299]] += 6.0 / (8.0 * scale)
+    k[:, :, 0] = b[:, None]
+    q, k, v = q.bfloat16(), k.bfloat16(), v.bfloat16()
+    idx = torch.arange(0, n, 3, dtype=torch.int32)
+    eo, else_ = oracle.sparse_attn(to_np(q), to_np(k), to_np(v), idx.numpy(), scale)
+    o, lse = _run_attn(q, k, v, idx, scale)
+    assert_rel_l2(o, eo, tag=f"rise {rise_nats}")
+    assert np.max(np.abs(lse - else_) / np.maximum(1.0, np.abs(else_))) <= 3e-5
+
+
+def test_attn_bf16_only_the_workgroups_that_need_it_are_redone():
+    """A handful of selected rows meet one key whose logit lies hundreds of nats above everything in their first
+    tile (their exponentials overflow under the first tile's offset), all other rows are ordinary.  The
+    workgroups holding those rows are redone by the exact launch, the others are not; every row, redone or not,
+    cut into key ranges or not, must match the oracle, and twice the same call the same bits."""
+    n, h, d, k_sel = 4100, 24, 128, 1100
+    q, k, v, idx = _attn_case(n, h, d, k_sel, torch.bfloat16, seed=404)
+    hot = idx[[3, 300, 1000, 1099]].long()            # rows of the first, second, fourth and last (cut) query tile
+    q[hot, :, 0] = 64.0
+    k[3000, :, 0] = 64.0                              # logit 4096 / sqrt(128) = 362 nats for the hot rows
+    k[17, 5, 0] = 48.0                                # and a second, smaller peak inside the first tile of head 5
+    scale = 1.0 / math.sqrt(d)
+    eo, else_ = oracle.sparse_attn(to_np(q), to_np(k), to_np(v), idx.numpy(), scale)
+    o, lse = _run_attn(q, k, v, idx, scale)
+    assert_rel_l2(o, eo, tag="hot rows among ordinary ones")
+    assert np.max(np.abs(lse - else_) / np.maximum(1.0, np.abs(else_))) <= 2e-2
+    o2, lse2 = _run_attn(q, k, v, idx, scale)
+    assert np.array_equal(o, o2) and np.array_equal(lse, lse2)
+
+
 @pytest.mark.parametrize("n,h,k_sel", [
     (4100, 24, 1100),     # 5 query tiles x 24 heads = 15 items per XCD: a partly filled round, cut in 2 key ranges
     (1500, 8, 256),       # 1 item per XCD, cut into as many key ranges as there are tiles allow
