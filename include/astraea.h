@@ -191,6 +191,18 @@ int astraea_scatter_update(void *cache, const void *src, astraea_dtype dt, int64
                            int64_t k_sel, int src_is_full, void *stream);
 
 /*
+ * astraea_kv_refresh - the cached keys and values of the selected tokens are replaced by this step's, the
+ * others keep what they hold (the configurations' "unselected tokens reuse cached K/V"; Algorithm 1 computes K
+ * and V before its attention step):
+ *     k_cache[idx_sel[r], :] = k_new[idx_sel[r], :],   v_cache[idx_sel[r], :] = v_new[idx_sel[r], :]
+ * The same as two astraea_scatter_update calls with src_is_full = 1, in one launch.  The four buffers are
+ * [N, row_elems] with a common row stride per side (elements); k_sel == 0 enqueues nothing.
+ */
+int astraea_kv_refresh(void *k_cache, void *v_cache, const void *k_new, const void *v_new, astraea_dtype dt, int64_t N,
+                       int64_t row_elems, int64_t cache_row_stride, int64_t src_row_stride, const int32_t *idx_sel,
+                       int64_t k_sel, void *stream);
+
+/*
  * astraea_sparse_linear - a layer that acts on each token by itself, evaluated for the selected
  * tokens only (Algorithm 1: Q = X_in[I_sel] W_Q; Sec. 3.2: such layers are computed for the selected
  * tokens and taken from the cache for the rest; FLOPs appendix: the projection and MLP terms, whose

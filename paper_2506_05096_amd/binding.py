@@ -26,7 +26,7 @@ CROSSOVER_UNIFORM, CROSSOVER_BLOCK = 0, 1
 
 EXPORTS = (
     "astraea_score", "astraea_select_topk", "astraea_select_topk_static", "astraea_sparse_attn_fwd", "astraea_sparse_attn_update_fwd",
-    "astraea_scatter_update", "astraea_gather_rows", "astraea_sparse_linear", "astraea_workspace_bytes", "astraea_budget_to_k", "astraea_attn_flops",
+    "astraea_scatter_update", "astraea_kv_refresh", "astraea_gather_rows", "astraea_sparse_linear", "astraea_workspace_bytes", "astraea_budget_to_k", "astraea_attn_flops",
     "astraea_probe_mfma_bf16", "astraea_probe_copy", "astraea_probe_kernel_timer", "astraea_probe_kernel_count",
     "astraea_probe_kernel_ms", "astraea_lse_weight_update", "astraea_attn_plan", "astraea_check_indices",
     "astraea_budget_search", "astraea_search_crossover", "astraea_search_mutate", "astraea_search_repair",
@@ -72,6 +72,8 @@ def lib() -> C.CDLL:
                                                      C.c_int, f32, vp, i64, vp, vp, sz, vp]
         L.astraea_scatter_update.argtypes = [vp, vp, C.c_int, i64, i64, i64, i64, vp, i64, C.c_int, vp]
         L.astraea_gather_rows.argtypes = [vp, vp, C.c_int, i64, i64, i64, i64, vp, i64, vp]
+        L.astraea_kv_refresh.argtypes = [vp, vp, vp, vp, C.c_int, i64, i64, i64, i64, vp, i64, vp]
+        L.astraea_kv_refresh.restype = C.c_int
         L.astraea_sparse_linear.argtypes = [vp, vp, vp, C.c_int, i64, i64, i64, i64, vp, i64, C.c_int, C.c_int, vp, i64,
                                             C.c_int, vp]
         L.astraea_sparse_linear.restype = C.c_int
@@ -209,6 +211,16 @@ def astraea_scatter_update(cache: torch.Tensor, src: torch.Tensor, idx_sel: torc
     _check(lib().astraea_scatter_update(_p(cache), _p(src), _dt(cache), cache.shape[0], cache.shape[1],
                                         cache.stride(0), src.stride(0), _p(idx_sel), k_sel, 1 if src_is_full else 0,
                                         _stream()))
+
+
+def astraea_kv_refresh(k_cache: torch.Tensor, v_cache: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor,
+                       idx_sel: torch.Tensor, k_sel: int) -> None:
+    for c, s in ((k_cache, k_new), (v_cache, v_new)):
+        assert c.dim() == 2 and s.dim() == 2 and c.stride(1) == 1 and s.stride(1) == 1 and c.shape == s.shape
+        assert c.dtype == s.dtype == k_cache.dtype
+    assert k_cache.shape == v_cache.shape and k_cache.stride(0) == v_cache.stride(0) and k_new.stride(0) == v_new.stride(0)
+    _check(lib().astraea_kv_refresh(_p(k_cache), _p(v_cache), _p(k_new), _p(v_new), _dt(k_cache), k_cache.shape[0],
+                                    k_cache.shape[1], k_cache.stride(0), k_new.stride(0), _p(idx_sel), k_sel, _stream()))
 
 
 def astraea_gather_rows(src: torch.Tensor, dst: torch.Tensor, idx_sel: torch.Tensor, k_sel: int) -> None:

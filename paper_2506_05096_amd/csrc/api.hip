@@ -229,6 +229,21 @@ int astraea_scatter_update(void *cache, const void *src, astraea_dtype dt, int64
                             N, true, src_is_full != 0, (hipStream_t)stream);
 }
 
+int astraea_kv_refresh(void *k_cache, void *v_cache, const void *k_new, const void *v_new, astraea_dtype dt, int64_t N,
+                       int64_t row_elems, int64_t cache_row_stride, int64_t src_row_stride, const int32_t *idx_sel,
+                       int64_t k_sel, void *stream)
+{
+    int rc = check_rows("astraea_kv_refresh", k_cache, k_new, dt, N, row_elems, cache_row_stride, src_row_stride, idx_sel,
+                        k_sel);
+    if (rc == ASTRAEA_OK)
+        rc = check_rows("astraea_kv_refresh", v_cache, v_new, dt, N, row_elems, cache_row_stride, src_row_stride, idx_sel,
+                        k_sel);
+    if (rc != ASTRAEA_OK || k_sel == 0) return rc;
+    const int64_t es = (int64_t)esize(dt);
+    return launch_move_rows(k_cache, k_new, row_elems * es, cache_row_stride * es, src_row_stride * es, idx_sel, k_sel, N,
+                            true, true, (hipStream_t)stream, v_cache, v_new);
+}
+
 int astraea_gather_rows(const void *src, void *dst, astraea_dtype dt, int64_t N, int64_t row_elems,
                         int64_t src_row_stride, int64_t dst_row_stride, const int32_t *idx_sel, int64_t k_sel,
                         void *stream)

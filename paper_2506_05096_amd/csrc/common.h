@@ -32,9 +32,10 @@ int topk_static_scratch(void **ptr_out);      // the library's own per-device sc
 int launch_select_topk(const float *score, int64_t N, int64_t k, int32_t *idx_sel, int32_t *idx_remain,
                        uint8_t *sel_mask, int32_t *skip_count, void *workspace, hipStream_t stream);
 
+// dst_b / src_b: an optional second buffer pair of the same shape and strides, moved by the same launch
 int launch_move_rows(void *dst, const void *src, int64_t row_bytes, int64_t dst_stride_bytes,
                      int64_t src_stride_bytes, const int32_t *idx, int64_t k_sel, int64_t n_rows, bool index_dst,
-                     bool index_src, hipStream_t stream);
+                     bool index_src, hipStream_t stream, void *dst_b = nullptr, const void *src_b = nullptr);
 
 int launch_check_indices(const int32_t *idx_sel, int64_t k_sel, int64_t N, int32_t *counts, hipStream_t stream);
 

@@ -19,11 +19,16 @@ constexpr int kRowsPerBlock = 4;      // one wave per row
 
 template <typename V> __device__ __forceinline__ V load_once(const V *p) { return __builtin_nontemporal_load(p); }
 
+// blockIdx.y picks one of up to two (destination, source) buffer pairs that share shape, strides and index list:
+// the K and the V cache of a layer are refreshed by one launch.
 template <typename V>
 __global__ __launch_bounds__(kRowsPerBlock *kWave) void move_rows_kernel(
-    char *__restrict__ dst, const char *__restrict__ src, int64_t row_bytes, int64_t dst_stride, int64_t src_stride,
+    char *__restrict__ dst0, const char *__restrict__ src0, char *__restrict__ dst1, const char *__restrict__ src1,
+    int64_t row_bytes, int64_t dst_stride, int64_t src_stride,
     const int32_t *__restrict__ idx, int64_t k_sel, int64_t n_rows, int index_dst, int index_src)
 {
+    char *__restrict__ dst = blockIdx.y ? dst1 : dst0;
+    const char *__restrict__ src = blockIdx.y ? src1 : src0;
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t r = (int64_t)blockIdx.x * kRowsPerBlock + threadIdx.x / kWave;
     if (r >= k_sel) return;
@@ -105,21 +110,24 @@ int launch_lse_weight_update(const float *lse_sel, int32_t H, int64_t N, const i
 
 int launch_move_rows(void *dst, const void *src, int64_t row_bytes, int64_t dst_stride_bytes,
                      int64_t src_stride_bytes, const int32_t *idx, int64_t k_sel, int64_t n_rows, bool index_dst,
-                     bool index_src, hipStream_t stream)
+                     bool index_src, hipStream_t stream, void *dst_b, const void *src_b)
 {
     if (k_sel == 0 || row_bytes == 0) return ASTRAEA_OK;
-    dim3 grid((unsigned)((k_sel + kRowsPerBlock - 1) / kRowsPerBlock)), block(kRowsPerBlock * kWave);
-    const uintptr_t all = (uintptr_t)dst | (uintptr_t)src | (uintptr_t)row_bytes | (uintptr_t)dst_stride_bytes |
-                          (uintptr_t)src_stride_bytes;
+    dim3 grid((unsigned)((k_sel + kRowsPerBlock - 1) / kRowsPerBlock), dst_b ? 2u : 1u), block(kRowsPerBlock * kWave);
+    const uintptr_t all = (uintptr_t)dst | (uintptr_t)src | (uintptr_t)dst_b | (uintptr_t)src_b | (uintptr_t)row_bytes |
+                          (uintptr_t)dst_stride_bytes | (uintptr_t)src_stride_bytes;
     if (all % 16 == 0)
-        hipLaunchKernelGGL(move_rows_kernel<uint4v>, grid, block, 0, stream, (char *)dst, (const char *)src, row_bytes,
-                           dst_stride_bytes, src_stride_bytes, idx, k_sel, n_rows, (int)index_dst, (int)index_src);
+        hipLaunchKernelGGL(move_rows_kernel<uint4v>, grid, block, 0, stream, (char *)dst, (const char *)src, (char *)dst_b,
+                           (const char *)src_b, row_bytes, dst_stride_bytes, src_stride_bytes, idx, k_sel, n_rows,
+                           (int)index_dst, (int)index_src);
     else if (all % 4 == 0)
-        hipLaunchKernelGGL(move_rows_kernel<uint32_t>, grid, block, 0, stream, (char *)dst, (const char *)src,
-                           row_bytes, dst_stride_bytes, src_stride_bytes, idx, k_sel, n_rows, (int)index_dst, (int)index_src);
+        hipLaunchKernelGGL(move_rows_kernel<uint32_t>, grid, block, 0, stream, (char *)dst, (const char *)src, (char *)dst_b,
+                           (const char *)src_b, row_bytes, dst_stride_bytes, src_stride_bytes, idx, k_sel, n_rows,
+                           (int)index_dst, (int)index_src);
     else
-        hipLaunchKernelGGL(move_rows_kernel<uint16_t>, grid, block, 0, stream, (char *)dst, (const char *)src,
-                           row_bytes, dst_stride_bytes, src_stride_bytes, idx, k_sel, n_rows, (int)index_dst, (int)index_src);
+        hipLaunchKernelGGL(move_rows_kernel<uint16_t>, grid, block, 0, stream, (char *)dst, (const char *)src, (char *)dst_b,
+                           (const char *)src_b, row_bytes, dst_stride_bytes, src_stride_bytes, idx, k_sel, n_rows,
+                           (int)index_dst, (int)index_src);
     return check_launch("astraea row move");
 }
 

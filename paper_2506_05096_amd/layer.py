@@ -46,8 +46,8 @@ class LayerStep:
 
     def step_kv_refresh(self, t: Dict[str, torch.Tensor], k: int) -> None:
         N, E = self.N, self.H * self.D
-        ab.astraea_scatter_update(t["k_cache"].view(N, E), t["k_new"].view(N, E), self.idx_sel, k, src_is_full=True)
-        ab.astraea_scatter_update(t["v_cache"].view(N, E), t["v_new"].view(N, E), self.idx_sel, k, src_is_full=True)
+        ab.astraea_kv_refresh(t["k_cache"].view(N, E), t["v_cache"].view(N, E), t["k_new"].view(N, E),
+                              t["v_new"].view(N, E), self.idx_sel, k)
 
     def step_attn(self, t: Dict[str, torch.Tensor], k: int, lse: Optional[torch.Tensor] = None) -> None:
         ab.astraea_sparse_attn_fwd(t["q"], t["k_cache"], t["v_cache"], self.idx_sel, k, self.o_sel[:max(k, 1)],

@@ -104,6 +104,18 @@ def test_select_topk_rejects_bad_arguments(L):
     assert f(None, 0, 0, None, None, None, None, None, 0, None) == ab.OK
 
 
+def test_kv_refresh_rejects_bad_arguments(L):
+    f = L.astraea_kv_refresh
+    f.restype = C.c_int
+    assert f(FAKE, FAKE, FAKE, FAKE, 9, 100, 64, 64, 64, FAKE, 10, None) == ab.ERR_UNSUPPORTED
+    assert f(FAKE, FAKE, FAKE, FAKE, ab.BF16, 100, 64, 32, 64, FAKE, 10, None) == ab.ERR_INVALID      # stride < row
+    assert f(FAKE, None, FAKE, FAKE, ab.BF16, 100, 64, 64, 64, FAKE, 10, None) == ab.ERR_INVALID      # a NULL buffer
+    assert f(FAKE, FAKE, FAKE, None, ab.BF16, 100, 64, 64, 64, FAKE, 10, None) == ab.ERR_INVALID
+    assert f(FAKE, FAKE, FAKE, FAKE, ab.BF16, 100, 64, 64, 64, None, 10, None) == ab.ERR_INVALID      # no index list
+    assert f(FAKE, FAKE, FAKE, FAKE, ab.BF16, 100, 64, 64, 64, FAKE, 101, None) == ab.ERR_INVALID     # k_sel > N
+    assert f(None, None, None, None, ab.BF16, 100, 64, 64, 64, None, 0, None) == ab.OK                 # budget 0
+
+
 def test_sparse_attn_rejects_bad_arguments(L):
     f = L.astraea_sparse_attn_fwd
 

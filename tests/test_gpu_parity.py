@@ -197,6 +197,28 @@ def test_scatter_and_gather_bit_exact(dtype, e):
     assert np.array_equal(to_np(dst), oracle.gather(to_np(full), idx.numpy()))
 
 
+@pytest.mark.parametrize("dtype,e,pad", [(torch.bfloat16, 3072, 0), (torch.float32, 512, 0), (torch.bfloat16, 5, 3),
+                                         (torch.bfloat16, 264, 8), (torch.float32, 3, 0)])
+def test_kv_refresh_bit_exact(dtype, e, pad):
+    """The K and V rows of the selected tokens in one launch: both caches equal what the oracle's cache merge
+    gives buffer by buffer, rows of other tokens and the padding of wider rows keep their bits, budget 0 moves
+    nothing."""
+    g = torch.Generator().manual_seed(e + pad)
+    n, k = 901, 333
+    kc, vc, kn, vn = (torch.randn(n, e + pad, generator=g).to(dtype) for _ in range(4))
+    idx = torch.randperm(n, generator=g)[:k].sort().values.to(torch.int32)
+    ek, ev = to_np(kc).copy(), to_np(vc).copy()
+    oracle.scatter(ek[:, :e], to_np(kn)[:, :e], idx.numpy(), src_is_full=True)
+    oracle.scatter(ev[:, :e], to_np(vn)[:, :e], idx.numpy(), src_is_full=True)
+    dk, dv = kc.to(DEV), vc.to(DEV)
+    ab.astraea_kv_refresh(dk[:, :e], dv[:, :e], kn.to(DEV)[:, :e], vn.to(DEV)[:, :e], idx.to(DEV), k)
+    _sync()
+    assert np.array_equal(to_np(dk), ek) and np.array_equal(to_np(dv), ev)
+    ab.astraea_kv_refresh(dk[:, :e], dv[:, :e], vn.to(DEV)[:, :e], kn.to(DEV)[:, :e], idx.to(DEV), 0)
+    _sync()
+    assert np.array_equal(to_np(dk), ek) and np.array_equal(to_np(dv), ev)
+
+
 # -------------------------------------------------------------- attention --
 
 def _attn_case(n, h, d, k_sel, dtype, seed, bias_std=0.0):
