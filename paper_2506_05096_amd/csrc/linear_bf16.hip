@@ -45,12 +45,20 @@ constexpr int kSbM = 8, kSbN = 4;        // tiles of one XCD round: 8 token tile
 // Waits until only the two most recent vector-memory instructions (the L2 warm-up loads) are pending:
 // the counter retires loads in order, so everything issued before them has then landed.
 __device__ __forceinline__ void wait_dma_keep2() { asm volatile("s_waitcnt vmcnt(2)" ::: "memory"); }
-// A 4-byte load whose only purpose is to pull its 128-byte line into L2.  `sink` must stay live until
-// the load has been waited for (the data lands in it whenever it arrives).
-__device__ __forceinline__ void touch_line(const void *gbase, uint32_t goff, uint32_t &sink)
+// A 4-byte load per lane whose only purpose is to pull its 128-byte line into L2.  It is the copy form
+// of the load (global -> LDS), aimed at a 256-byte scrap area every wave may scribble on: the data lands
+// whenever it arrives, and with no register as its destination nothing the compiler does with registers
+// in the meantime can be hit by it.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"    // m0 is a reserved register; naming it as clobbered is the point
+__device__ __forceinline__ void touch_line(const void *gbase, uint32_t goff, uint32_t lds_scrap)
 {
-    asm volatile("global_load_dword %0, %1, %2" : "+v"(sink) : "v"(goff), "s"(gbase) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+                 :
+                 : "s"(lds_scrap), "v"(goff), "s"(gbase)
+                 : "memory", "m0");
 }
+#pragma clang diagnostic pop
 
 struct LinearArgs {
     const __bf16 *x;
@@ -71,6 +79,7 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void linear_bf16_kernel(LinearArg
     constexpr int kPitch = 272;          // epilogue staging: 128 features of a token, padded
     constexpr int kEpiBytes = kWaves * 64 * kPitch;   // every wave stages 64 tokens at a time
     __shared__ __attribute__((aligned(1024))) char lds[2 * kStageBytes > kEpiBytes ? 2 * kStageBytes : kEpiBytes];
+    __shared__ __attribute__((aligned(256))) uint32_t scrap[kWave];      // where the L2 warm-up loads land
 
     // ---- which tile: workgroup ids reach the XCDs round-robin; each XCD takes every 8th super-block
     // of 8 x 4 tiles and runs its 32 tiles at the same time.
@@ -136,7 +145,7 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void linear_bf16_kernel(LinearArg
         pf_x = (uint32_t)(row * a.ldx * 2);
     }
     asm volatile("" ::"v"(pf_x), "v"(pf_w));
-    uint32_t sink_w = 0, sink_x = 0;
+    const uint32_t scrap0 = (uint32_t)(uintptr_t)scrap;
     constexpr int kPrefetch = 3;
     auto dma_w = [&](int t, int kstep, uint32_t stage) __attribute__((always_inline)) {
         dma16(wg + (int64_t)kstep * kRowBytes, woff[t], lds0 + stage + (cw + kCopyWaves * t) * 1024);
@@ -172,8 +181,8 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void linear_bf16_kernel(LinearArg
         }
         for (int p = 1; p < kPrefetch; ++p) {
             const int kp = p < nk ? p : nk - 1;
-            touch_line(wg + (int64_t)kp * kRowBytes, pf_w, sink_w);
-            touch_line(xg + (int64_t)kp * kRowBytes, pf_x, sink_x);
+            touch_line(wg + (int64_t)kp * kRowBytes, pf_w, scrap0);
+            touch_line(xg + (int64_t)kp * kRowBytes, pf_x, scrap0);
         }
     }
     wait_dma();
@@ -193,8 +202,8 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void linear_bf16_kernel(LinearArg
                 dma_w(t, kn, next_stage);
                 dma_x(t, kn, next_stage);
             }
-            touch_line(wg + (int64_t)kp * kRowBytes, pf_w, sink_w);
-            touch_line(xg + (int64_t)kp * kRowBytes, pf_x, sink_x);
+            touch_line(wg + (int64_t)kp * kRowBytes, pf_w, scrap0);
+            touch_line(xg + (int64_t)kp * kRowBytes, pf_x, scrap0);
         }
         bf16x8 wf[2][4], xf[2][kTb];
 #pragma unroll
@@ -243,7 +252,6 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void linear_bf16_kernel(LinearArg
     }
 
     wait_dma();
-    asm volatile("" ::"v"(sink_w), "v"(sink_x));
     // ---- epilogue: bias, activation, bf16; then through LDS so that global stores cover whole rows.
     // Register group g of block (i, j): features 128*wn + 32*i + 8*g + 4*hf + 0..3, token
     // 32*kTb*wm + 32*j + qc of the tile.  An accumulator lane owns one token, so stores straight from the
@@ -324,6 +332,7 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void linear_bf16_kernel(LinearArg
         __builtin_amdgcn_s_waitcnt(0xc07f);                      // reads done before the second half overwrites
     }
 }
+
 
 }  // namespace
 

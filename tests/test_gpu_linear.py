@@ -90,6 +90,37 @@ def test_sparse_linear_all_row_modes_agree_bit_for_bit():
     assert np.array_equal(to_np(y2), to_np(y3))
 
 
+@pytest.mark.parametrize("n,cin,cout,k_sel,act", [
+    (9000, 256, 4104, 8200, ab.ACT_GELU_TANH),     # 33 x 17 tiles, both ragged, a short contraction
+    (70000, 384, 3072, 33000, ab.ACT_NONE),        # 129 x 12 tiles: the super-block rows end in a partly filled one
+])
+def test_sparse_linear_many_tiles_per_compute_unit(n, cin, cout, k_sel, act):
+    """Shapes with several tiles per compute unit (several rounds of workgroups, super-block rows that end in a
+    partly filled one): gathered input, rows scattered into a wider cached buffer, ragged last tiles in both
+    directions.  Checked against the oracle on sampled rows (all features), for untouched rows and padding in
+    full, and against the compact form bit for bit."""
+    x, w, b, idx = _case(n, cin, cout, k_sel, seed=n + cout)
+    pad = 24
+    g = torch.Generator().manual_seed(5)
+    cache0 = torch.randn(n, cout + pad, generator=g).bfloat16()
+    cache = cache0.to(DEV)
+    dx, dw, db, di = x.to(DEV), w.to(DEV), b.to(DEV), idx.to(DEV)
+    ab.astraea_sparse_linear(dx, dw, db, di, k_sel, cache[:, :cout], act=act, y_is_compact=False)
+    y = torch.full((k_sel, cout), float("nan"), dtype=torch.bfloat16, device=DEV)
+    ab.astraea_sparse_linear(dx, dw, db, di, k_sel, y, act=act)
+    torch.cuda.synchronize()
+    c, yc = to_np(cache), to_np(y)
+    assert np.array_equal(c[idx.numpy()][:, :cout], yc)
+    rest = np.setdiff1d(np.arange(n), idx.numpy())
+    assert np.array_equal(c[rest], to_np(cache0)[rest]) and np.array_equal(c[:, cout:], to_np(cache0)[:, cout:])
+    rng = np.random.default_rng(1)
+    rows = np.unique(np.concatenate([[0, 1, 255, 256, 257, k_sel - 257, k_sel - 256, k_sel - 2, k_sel - 1],
+                                     (k_sel // 256) * 256 + np.array([-1, 0, 1]), rng.integers(0, k_sel, 300)]))
+    rows = rows[(rows >= 0) & (rows < k_sel)]
+    ref = oracle.sparse_linear(to_np(x)[idx.numpy()[rows]], to_np(w), None, bias=to_np(b), act=act, x_is_compact=True)
+    _check(yc[rows], ref, cin)
+
+
 def test_sparse_linear_closed_forms_on_gpu():
     n, c = 500, 256
     g = torch.Generator().manual_seed(3)
