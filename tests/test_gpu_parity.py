@@ -139,6 +139,27 @@ def test_topk_on_both_sides_of_the_single_workgroup_limit(kind, n):
         assert np.array_equal(skip, oracle.update_skip_count(skip0, e_mask)), (kind, n, k)
 
 
+@pytest.mark.parametrize("n", [40001, 118800])
+def test_topk_scores_that_are_not_16_byte_aligned(n):
+    """The score array only has to be 4-byte aligned: one that starts 4 bytes into an allocation (and has an odd
+    length) must give the same selection."""
+    s = synth.random_scores(n + 1, 29 + n, "narrow")
+    k = (3 * n) // 10
+    e_idx, e_rem, e_mask = oracle.topk(s.numpy()[1:], k)
+    ds = s.to(DEV)[1:]
+    assert ds.data_ptr() % 16 == 4
+    ws = torch.empty(ab.workspace_bytes(ab.OP_SELECT_TOPK, n), dtype=torch.uint8, device=DEV)
+    idx = torch.full((k,), -7, dtype=torch.int32, device=DEV)
+    rem = torch.full((n - k,), -7, dtype=torch.int32, device=DEV)
+    mask = torch.full((n,), 9, dtype=torch.uint8, device=DEV)
+    _check_rc = ab.lib().astraea_select_topk(ds.data_ptr(), n, k, idx.data_ptr(), rem.data_ptr(), mask.data_ptr(), None,
+                                             ws.data_ptr(), ws.numel(), torch.cuda.current_stream().cuda_stream)
+    assert _check_rc == ab.OK
+    _sync()
+    assert np.array_equal(idx.cpu().numpy(), e_idx) and np.array_equal(rem.cpu().numpy(), e_rem)
+    assert np.array_equal(mask.cpu().numpy(), e_mask)
+
+
 def test_topk_special_values():
     s = torch.tensor([float("nan"), -0.0, 0.0, float("inf"), -float("inf"), 1.0, float("nan"), 0.0, -1e-45, 1e-45,
                       3.4e38, -3.4e38])

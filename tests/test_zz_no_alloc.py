@@ -38,9 +38,9 @@ def _both(score, k):
 
 def test_static_scratch_selection_equals_the_workspace_one_on_calls_in_a_row():
     # sizes above 32768 take the multi-launch path, the one that uses the scratch array; the sequence shrinks,
-    # grows again and ends on a single-workgroup size
-    cases = [(118800, 35640, "narrow"), (50000, 20000, "tied"), (40000, 0, "normal"), (131072, 131072, "lognormal"),
-             (33000, 1, "narrow"), (5000, 1234, "tied")]
+    # grows again and ends on a single-workgroup size (which leaves the array alone)
+    cases = [(1000000, 300000, "narrow"), (118800, 35640, "narrow"), (50000, 20000, "tied"), (40000, 0, "normal"),
+             (524288, 524288, "lognormal"), (33000, 1, "narrow"), (5000, 1234, "tied")]
     for n, k, kind in cases:
         a, b = _both(synth.random_scores(n, 17 + n, kind), k)
         for x, y, what in zip(a, b, ("idx_sel", "idx_remain", "sel_mask", "skip_count")):
