@@ -310,8 +310,9 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
     constexpr int kAhead = 4;      // an MFMA's fragment is fetched kAhead MFMAs before it issues
     // MFMA phase.  O^T += V^T(j) P^T(j): 16 MFMAs; group tt contracts the 16 keys 16*tt + {0..3, 8..11}
     // (lanes 0-31) and 16*tt + {4..7, 12..15} (lanes 32-63); V^T(j) is in the parity va[] points at.
-    // Then, if WITH_QK, S^T = K Q^T for the tile in the parity ka[] points at: 16 MFMAs, two blocks
-    // of 32 keys.  One LDS read pipeline runs through all 32 MFMAs.
+    // Then, if WITH_QK, S^T = K Q^T for the next tile: 16 MFMAs, the two blocks of 32 keys taking turns (two
+    // consecutive MFMAs share the Q fragment and feed different accumulators).  One LDS read pipeline runs
+    // through all 32 MFMAs.
     // The buffer parity PAR of the phase is a compile-time constant: V^T(j) is read from buffer pair PAR, K(j+1)
     // from pair PAR ^ 1.
     auto mfma_phase = [&](auto qk_tag, auto par_tag) __attribute__((always_inline)) {
@@ -330,7 +331,7 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
             if (n < 16)
                 vf[n] = lds_read_b128(lds0 + va[n >> 2] + (VP + (n & 3) * 32 * 128));
             else if (WITH_QK)
-                kf[n - 16] = lds_read_b128(lds0 + ka[(n - 16) & 7] + (KP + ((n - 16) >> 3) * 32 * kRowBytes));
+                kf[n - 16] = lds_read_b128(lds0 + ka[(n - 16) >> 1] + (KP + ((n - 16) & 1) * 32 * kRowBytes));
         }
         if (WITH_QK) {
 #pragma unroll
@@ -340,9 +341,9 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void attn_bf16_kernel(
             }
 #pragma unroll
             for (int u = 0; u < 16; ++u) {
-                sacc[u >> 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[u], qf[u & 7], sacc[u >> 3], 0, 0, 0);
+                sacc[u & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[u], qf[u >> 1], sacc[u & 1], 0, 0, 0);
                 const int n = u + kAhead;
-                if (n < 16) kf[n] = lds_read_b128(lds0 + ka[n & 7] + (KP + (n >> 3) * 32 * kRowBytes));
+                if (n < 16) kf[n] = lds_read_b128(lds0 + ka[n >> 1] + (KP + (n & 1) * 32 * kRowBytes));
             }
         }
         SGB(DSR, kAhead);
