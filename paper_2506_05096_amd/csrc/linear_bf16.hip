@@ -13,14 +13,19 @@
 //    features per register group: the epilogue packs them to 8-byte stores along the output row.
 //  * workgroup = 8 waves, two per SIMD, output tile 256 features x 256 tokens, each wave 128 features
 //    x 64 tokens (4 x 2 MFMA blocks, 128 accumulator registers, 3 LDS fragment reads per 4 MFMAs).
-//    One wave per SIMD with 128 x 128 (kWaves = 4) reads less from LDS but leaves the matrix pipe idle
-//    at every barrier; measured 2-4 % slower.
+//    One wave per SIMD with 128 x 128 (kWaves = 4, every wave copying, the step's barrier moved in
+//    front of the last quarter so that no fragment read follows it) runs fewer clocks per step at a
+//    lower clock rate, or the other way round: the chip holds its power limit and the two designs
+//    end up within 1 % of each other.
 //  * the contraction advances in steps of 64; the two 32 KiB tiles of a step go from global memory
 //    straight into LDS (global_load_lds_dwordx4, per-lane addresses, so the row gather costs nothing),
 //    double buffered, 16-byte chunks XOR-swizzled inside each 128-byte row against bank conflicts.
-//    The second wave of each SIMD issues all copy instructions of the next step while it waits for the
-//    matrix pipe, and a 4-byte load per row touches the lines of three steps ahead so that the copies
-//    hit in L2.
+//    A copy must cover whole 128-byte lines: with 64-byte pieces (a ring of four 32-deep units) the
+//    L1 fetches every line from L2 twice and the kernel is 30 % slower.
+//    The second wave of each SIMD issues the copy instructions of the next step, one behind each of
+//    its first 16 MFMAs, and has the higher priority: the memory pipe holds it at every copy, and its
+//    neighbour's MFMAs fill exactly that time.  A 4-byte load per row touches the lines of three
+//    steps ahead so that the copies hit in L2.
 //  * workgroup ids are mapped so that the 32 workgroups resident on one XCD form an 8 x 4 block of
 //    tiles: they stream 8 row tiles and 4 weight tiles through that XCD's L2 instead of 32 + 32.
 #include "gfx950.h"
@@ -35,7 +40,7 @@ constexpr int kBk = 64;                  // contraction step
 constexpr int kRowBytes = kBk * 2;       // 128 B of a row per step
 constexpr int kTileBytes = 256 * kRowBytes;          // 32 KiB
 constexpr int kStageBytes = 2 * kTileBytes;          // w tile, then x tile
-constexpr int kWaves = 8;                // 8: two per SIMD, 128 features x 64 tokens each; 4: one per SIMD, 128 x 128 each
+constexpr int kWaves = 8;                // two per SIMD, 128 features x 64 tokens each
 constexpr int kTb = 16 / kWaves;         // 32-token MFMA blocks per wave
 constexpr int kCopyWaves = kWaves / 2;   // the waves that issue the tile copies (the second wave of each SIMD)
 constexpr int kCopies = 32 / kCopyWaves; // 1 KiB copy instructions per copying wave and tile
@@ -80,6 +85,10 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void linear_bf16_kernel(LinearArg
     constexpr int kEpiBytes = kWaves * 64 * kPitch;   // every wave stages 64 tokens at a time
     __shared__ __attribute__((aligned(1024))) char lds[2 * kStageBytes > kEpiBytes ? 2 * kStageBytes : kEpiBytes];
     __shared__ __attribute__((aligned(256))) uint32_t scrap[kWave];      // where the L2 warm-up loads land
+    // destination rows and bias of this tile, fetched while the first step's tiles are on their way: the
+    // epilogue then reads them from LDS instead of waiting for global loads three times over
+    __shared__ int32_t tile_rows[kBm];
+    __shared__ __attribute__((aligned(16))) uint16_t tile_bias[kBn];
 
     // ---- which tile: workgroup ids reach the XCDs round-robin; each XCD takes every 8th super-block
     // of 8 x 4 tiles and runs its 32 tiles at the same time.
@@ -95,19 +104,34 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void linear_bf16_kernel(LinearArg
     const int qc = lane & 31, hf = lane >> 5;
     const int wn = wave & 1, wm = wave >> 1;          // this wave's 128 features and 32*kTb tokens of the tile
     const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
+    // thread t < 256: destination row of the tile's token t (-1: not stored) and bias of its feature t
+    int32_t my_row = -1;
+    uint16_t my_bias = 0;
+    if (tid < kBm) {
+        const int m = m0 + tid;
+        if (m < a.k_sel) {
+            my_row = m;
+            if (a.y_indexed) {
+                const int32_t ix = a.idx_sel[m];
+                my_row = (uint32_t)ix < (uint32_t)a.n_rows ? ix : -1;
+            }
+        }
+        const int n = n0 + tid;
+        if (a.bias && n < a.c_out) my_bias = reinterpret_cast<const uint16_t *>(a.bias)[n];
+    }
 
-    // ---- tile copies.  The two waves of a SIMD take the matrix pipe one after the other, not cycle by
-    // cycle: the first wave (made so by its raised priority) runs its MFMAs of a step while the second
-    // waits for the pipe.  The memory pipe accepts a 1 KiB copy instruction only every ~16 clocks per CU,
-    // so issuing the 64 of a step stalls whoever does it; the second waves do all of it, in the time
-    // they would spend waiting anyway, and the first waves start their MFMAs right after the barrier.
+    // ---- tile copies.  The memory pipe accepts a 1 KiB copy instruction only every ~16 clocks per CU
+    // (~57 per wave with four waves at it), so the 64 of a step hold whoever issues them for half a step.
+    // The second wave of each SIMD does all of it, one copy behind each of its first 16 MFMAs, and runs at
+    // the higher priority: while it is held at a copy the first wave's MFMAs have the matrix pipe, and
+    // when it is not, its own go first.  Both waves end their step at about the same time.
     // One instruction fills 8 rows of a tile; copying wave c = wave - 4 issues instructions c, c+4, ...,
     // c+28 of each tile.  Lane l serves row 8*i + l/8 and the physical chunk l%8, which holds logical
     // chunk (l%8) ^ ((row/2)%8); for the rows of one wave that is the same in all 8 instructions, so a
     // lane's byte offset inside its rows is fixed.
     const bool copier = wave >= kCopyWaves;
     const int cw = wave & (kCopyWaves - 1);
-    if (!copier) __builtin_amdgcn_s_setprio(1);
+    if (copier) __builtin_amdgcn_s_setprio(1);
     const int d_row = lane >> 3;
     const int lchunk = (lane & 7) ^ ((4 * (cw & 1) + (lane >> 4)) & 7);
     uint32_t woff[kCopies], xoff[kCopies];   // byte offsets of this lane's rows from w and x
@@ -186,63 +210,72 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void linear_bf16_kernel(LinearArg
         }
     }
     wait_dma();
+    if (tid < kBm) {
+        tile_rows[tid] = my_row;
+        tile_bias[tid] = my_bias;
+    }
     __builtin_amdgcn_s_barrier();
 
+    bf16x8 wf[2][4], xf[2][kTb];
+    auto read_first = [&](uint32_t flip) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < kTb; ++j) xf[0][j] = lds_read_b128(lds0 + (xa[0] ^ flip) + j * 32 * kRowBytes);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) wf[0][i] = lds_read_b128(lds0 + (wa[0] ^ flip) + i * 32 * kRowBytes);
+    };
+#define SB() __builtin_amdgcn_sched_barrier(0)
     uint32_t next_stage = kStageBytes;   // where the copies of step kk+1 go
+    int kn = 0, kp = 0;
+    // Quarter s of a step, in the order written: behind each of its first MFMAs one fragment read of quarter
+    // s + 1; a copying wave also puts one tile copy behind each MFMA of quarters 0 and 1 and the two warm-up
+    // loads into quarter 2.  The memory pipe takes a copy every ~16 clocks per CU, ~57 per wave with four
+    // waves at it, so a copying wave spends half a step held up at its copies; its SIMD neighbour's MFMAs
+    // run in exactly that time.
+    auto quarter = [&](auto s_tag) __attribute__((always_inline)) {
+        constexpr int s = decltype(s_tag)::value;
+        constexpr int cur = s & 1, nxt = cur ^ 1;
+#pragma unroll
+        for (int n = 0; n < 4 * kTb; ++n) {
+            const int i = n / kTb, j = n % kTb;
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[cur][i], xf[cur][j], acc[i][j], 0, 0, 0);
+            if (s < 3) {
+                if (n < kTb) xf[nxt][n] = lds_read_b128(lds0 + xa[(s + 1) & 3] + n * 32 * kRowBytes);
+                else if (n < kTb + 4) wf[nxt][n - kTb] = lds_read_b128(lds0 + wa[(s + 1) & 3] + (n - kTb) * 32 * kRowBytes);
+            }
+            if (s < 2) {
+                const int c = s * 4 * kTb + n;          // 0 .. 15
+                if (copier) {
+                    if (c & 1) dma_x(c >> 1, kn, next_stage);
+                    else dma_w(c >> 1, kn, next_stage);
+                }
+            } else if (s == 2 && n < 2) {
+                if (copier) {
+                    if (n == 0) touch_line(wg + (int64_t)kp * kRowBytes, pf_w, scrap0);
+                    else touch_line(xg + (int64_t)kp * kRowBytes, pf_x, scrap0);
+                }
+            }
+            SB();
+        }
+    };
+    using Q0 = std::integral_constant<int, 0>;
+    using Q1 = std::integral_constant<int, 1>;
+    using Q2 = std::integral_constant<int, 2>;
+    using Q3 = std::integral_constant<int, 3>;
     for (int kk = 0; kk < nk; ++kk) {
         // the last step has nothing to prefetch: it copies its own tiles again into the idle stage
         // rather than branch around every copy
-        const int kn = kk + 1 < nk ? kk + 1 : kk;
-        const int kp = kk + kPrefetch < nk ? kk + kPrefetch : nk - 1;
-        if (copier) {
-            // all of the next step's copies, then the warm-up loads (after the copies, so that waiting for
-            // the copies leaves them pending)
-#pragma unroll
-            for (int t = 0; t < kCopies; ++t) {
-                dma_w(t, kn, next_stage);
-                dma_x(t, kn, next_stage);
-            }
-            touch_line(wg + (int64_t)kp * kRowBytes, pf_w, scrap0);
-            touch_line(xg + (int64_t)kp * kRowBytes, pf_x, scrap0);
-        }
-        bf16x8 wf[2][4], xf[2][kTb];
-#pragma unroll
-        for (int j = 0; j < kTb; ++j) xf[0][j] = lds_read_b128(lds0 + xa[0] + j * 32 * kRowBytes);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) wf[0][i] = lds_read_b128(lds0 + wa[0] + i * 32 * kRowBytes);
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const int cur = s & 1, nxt = cur ^ 1;
-            if (s < 3) {
-                // x fragments first: every MFMA of the quarter needs them, the w fragments are needed one by one
-#pragma unroll
-                for (int j = 0; j < kTb; ++j) xf[nxt][j] = lds_read_b128(lds0 + xa[s + 1] + j * 32 * kRowBytes);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) wf[nxt][i] = lds_read_b128(lds0 + wa[s + 1] + i * 32 * kRowBytes);
-            }
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-#pragma unroll
-                for (int j = 0; j < kTb; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[cur][i], xf[cur][j], acc[i][j], 0, 0, 0);
-            }
-            // order inside the quarter: each fragment read of the next quarter goes out behind one MFMA of
-            // this one, i.e. a quarter ahead of its use (left alone, the scheduler sinks the reads to just
-            // before the MFMAs that need them and the wave waits out the LDS latency several times per quarter)
-            if (s < 3) {
-#pragma unroll
-                for (int r = 0; r < 4 + kTb; ++r) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
-                }
-                __builtin_amdgcn_sched_group_barrier(0x008, 4 * kTb - (4 + kTb), 0);
-            } else {
-                __builtin_amdgcn_sched_group_barrier(0x008, 4 * kTb, 0);
-            }
-        }
+        kn = kk + 1 < nk ? kk + 1 : kk;
+        kp = kk + kPrefetch < nk ? kk + kPrefetch : nk - 1;
+        read_first(0);
+        SB();
+        quarter(Q0{});
+        quarter(Q1{});
+        quarter(Q2{});
+        quarter(Q3{});
         // the next step's tiles are complete and this step's are no longer read: swap stages
         wait_dma_keep2();
         __builtin_amdgcn_s_barrier();
+        SB();
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             wa[s] ^= kStageBytes;
@@ -267,12 +300,8 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void linear_bf16_kernel(LinearArg
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            int n = n0 + wn * 128 + 32 * i + 8 * g + 4 * hf;
-            if (n > a.c_out - 4) n = a.c_out - 4;            // past the end: any valid address, the result is not stored
-            bias2[i][g] = uint2v{0u, 0u};
-            if (a.bias) bias2[i][g] = *reinterpret_cast<const uint2v *>(a.bias + n);
-        }
+        for (int g = 0; g < 4; ++g)
+            bias2[i][g] = *reinterpret_cast<const uint2v *>(&tile_bias[wn * 128 + 32 * i + 8 * g + 4 * hf]);
     const uint32_t ebase = lds0 + wave * (64 * kPitch);
     const int o_row = lane >> 4, o_chunk = lane & 15;      // read-back: 4 rows per instruction, 16 lanes x 16 B each
 #pragma unroll
@@ -307,27 +336,16 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void linear_bf16_kernel(LinearArg
         __builtin_amdgcn_s_waitcnt(0xc07f);                      // lgkmcnt(0): this wave's LDS writes are done
         // destination rows of this half first (16 per lane), then the stores: an index load between
         // two stores would be waited for each time
-        int64_t orow[16];
-#pragma unroll
-        for (int it = 0; it < 16; ++it) {
-            int m = m0 + wm * 32 * kTb + 64 * jh + 4 * it + o_row;
-            if (m > a.k_sel - 1) m = a.k_sel - 1;
-            orow[it] = m;
-            if (a.y_indexed) {
-                const int32_t ix = a.idx_sel[m];
-                orow[it] = (uint32_t)ix < (uint32_t)a.n_rows ? (int64_t)ix : -1;     // -1: not stored
-            }
-        }
 #pragma unroll
         for (int it = 0; it < 16; ++it) {
             const int tl = 4 * it + o_row;                       // token inside this half
-            const int m = m0 + wm * 32 * kTb + 64 * jh + tl;
+            const int64_t orow = tile_rows[wm * 32 * kTb + 64 * jh + tl];    // -1: past the end or a bad index
             const int n = n0 + wn * 128 + 8 * o_chunk;           // c_out is a multiple of 8: a chunk is all in or all out
             const uint4v val = *reinterpret_cast<const uint4v __attribute__((address_space(3))) *>(
                 (uintptr_t)(ebase + tl * kPitch + o_chunk * 16));
             // written once: streaming stores leave the tiles other workgroups still read in L2 (+1-3 %)
-            if (m < a.k_sel && n < a.c_out && orow[it] >= 0)
-                __builtin_nontemporal_store(val, reinterpret_cast<uint4v *>(a.y + orow[it] * a.ldy + n));
+            if (n < a.c_out && orow >= 0)
+                __builtin_nontemporal_store(val, reinterpret_cast<uint4v *>(a.y + orow * a.ldy + n));
         }
         __builtin_amdgcn_s_waitcnt(0xc07f);                      // reads done before the second half overwrites
     }

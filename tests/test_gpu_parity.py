@@ -390,6 +390,18 @@ def test_attn_bf16_only_the_workgroups_that_need_it_are_redone():
     assert np.max(np.abs(lse - else_) / np.maximum(1.0, np.abs(else_))) <= 2e-2
     o2, lse2 = _run_attn(q, k, v, idx, scale)
     assert np.array_equal(o, o2) and np.array_equal(lse, lse2)
+    # and written straight into a cached buffer: the same bits in the rows idx names, nothing else touched
+    g = torch.Generator().manual_seed(8)
+    cache0 = torch.randn(n, h * d, generator=g).bfloat16()
+    cache = cache0.to(DEV)
+    wsb = ab.workspace_bytes(ab.OP_SPARSE_ATTN, n, k_sel, h, d)
+    ws = torch.empty(wsb, dtype=torch.uint8, device=DEV)
+    ab.astraea_sparse_attn_update_fwd(q.to(DEV), k.to(DEV), v.to(DEV), idx.to(DEV), k_sel, cache, scale, workspace=ws)
+    _sync()
+    got = to_np(cache)
+    assert np.array_equal(as_f64(got[idx.numpy()]).reshape(k_sel, h, d), o)
+    rest = np.setdiff1d(np.arange(n), idx.numpy())
+    assert np.array_equal(got[rest], to_np(cache0)[rest])
 
 
 @pytest.mark.parametrize("n,h,k_sel", [
