@@ -24,7 +24,7 @@
 //    L1 fetches every line from L2 twice and the kernel is 30 % slower.
 //    The second wave of each SIMD issues the copy instructions of the next step, one behind each of
 //    its first 16 MFMAs, and has the higher priority: the memory pipe holds it at every copy, and its
-//    neighbour's MFMAs fill exactly that time.  A 4-byte load per row touches the lines of three
+//    neighbour's MFMAs fill exactly that time.  A 4-byte load per row touches the lines of two
 //    steps ahead so that the copies hit in L2.
 //  * workgroup ids are mapped so that the 32 workgroups resident on one XCD form an 8 x 4 block of
 //    tiles: they stream 8 row tiles and 4 weight tiles through that XCD's L2 instead of 32 + 32.
@@ -170,7 +170,7 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void linear_bf16_kernel(LinearArg
     }
     asm volatile("" ::"v"(pf_x), "v"(pf_w));
     const uint32_t scrap0 = (uint32_t)(uintptr_t)scrap;
-    constexpr int kPrefetch = 3;
+    constexpr int kPrefetch = 2;      // 3: 2-3 % slower, 1: the copy is already on its way
     auto dma_w = [&](int t, int kstep, uint32_t stage) __attribute__((always_inline)) {
         dma16(wg + (int64_t)kstep * kRowBytes, woff[t], lds0 + stage + (cw + kCopyWaves * t) * 1024);
     };
