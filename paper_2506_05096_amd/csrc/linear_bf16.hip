@@ -65,6 +65,9 @@ __device__ __forceinline__ void touch_line(const void *gbase, uint32_t goff, uin
 }
 #pragma clang diagnostic pop
 
+// Nothing moves across it: the order of MFMAs, fragment reads and copies inside a step is the written one.
+#define SB() __builtin_amdgcn_sched_barrier(0)
+
 struct LinearArgs {
     const __bf16 *x;
     const __bf16 *w;
@@ -217,13 +220,13 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void linear_bf16_kernel(LinearArg
     __builtin_amdgcn_s_barrier();
 
     bf16x8 wf[2][4], xf[2][kTb];
-    auto read_first = [&](uint32_t flip) __attribute__((always_inline)) {
+    // the fragments of a step's first quarter
+    auto read_first = [&]() __attribute__((always_inline)) {
 #pragma unroll
-        for (int j = 0; j < kTb; ++j) xf[0][j] = lds_read_b128(lds0 + (xa[0] ^ flip) + j * 32 * kRowBytes);
+        for (int j = 0; j < kTb; ++j) xf[0][j] = lds_read_b128(lds0 + xa[0] + j * 32 * kRowBytes);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) wf[0][i] = lds_read_b128(lds0 + (wa[0] ^ flip) + i * 32 * kRowBytes);
+        for (int i = 0; i < 4; ++i) wf[0][i] = lds_read_b128(lds0 + wa[0] + i * 32 * kRowBytes);
     };
-#define SB() __builtin_amdgcn_sched_barrier(0)
     uint32_t next_stage = kStageBytes;   // where the copies of step kk+1 go
     int kn = 0, kp = 0;
     // Quarter s of a step, in the order written: behind each of its first MFMAs one fragment read of quarter
@@ -266,7 +269,7 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void linear_bf16_kernel(LinearArg
         // rather than branch around every copy
         kn = kk + 1 < nk ? kk + 1 : kk;
         kp = kk + kPrefetch < nk ? kk + kPrefetch : nk - 1;
-        read_first(0);
+        read_first();
         SB();
         quarter(Q0{});
         quarter(Q1{});
@@ -294,8 +297,7 @@ __global__ __launch_bounds__(kWaves *kWave, 1) void linear_bf16_kernel(LinearArg
     // bytes) and writes 4 rows x 256 contiguous bytes per instruction.  The tile buffers are free: every
     // wave has passed the barrier that ends the last step.  The region is private to the wave, so no
     // workgroup barrier is needed, only the wave's own LDS counter.
-    // this lane's 64 bias values (16 groups of 4 features), fetched in one batch: a load inside the
-    // loops below would be waited for 64 times over
+    // this lane's 64 bias values (16 groups of 4 features), from the copy in LDS
     uint2v bias2[4][4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
