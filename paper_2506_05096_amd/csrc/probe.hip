@@ -45,11 +45,13 @@ __global__ __launch_bounds__(256) void mfma_loop_kernel(float *sink, int iters, 
     sink[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
 
+// One 16-byte vector per thread, streaming load and store: the fastest plain copy found on this chip
+// (6.2 - 6.6 TB/s read + write for 1 GiB; a grid-stride loop over 4096 workgroups reaches 4.6, eight vectors per
+// thread 5.4, the runtime's device-to-device copy 4.9).
 __global__ __launch_bounds__(256) void copy_kernel(const uint4v *__restrict__ src, uint4v *__restrict__ dst, size_t n)
 {
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (; i < n; i += stride) dst[i] = src[i];
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
 }  // namespace
@@ -77,8 +79,10 @@ int astraea_probe_copy(const void *src, void *dst, int64_t bytes, void *stream)
         return fail(ASTRAEA_ERR_INVALID, "astraea_probe_copy: pointers and size must be multiples of 16 bytes");
     if (bytes == 0) return ASTRAEA_OK;
     if (!src || !dst) return fail(ASTRAEA_ERR_INVALID, "astraea_probe_copy: NULL pointer");
-    hipLaunchKernelGGL(copy_kernel, dim3(4096), dim3(256), 0, (hipStream_t)stream, (const uint4v *)src, (uint4v *)dst,
-                       (size_t)(bytes / 16));
+    const size_t n = (size_t)(bytes / 16);
+    if ((n + 255) / 256 > 2147483647ull) return fail(ASTRAEA_ERR_INVALID, "astraea_probe_copy: more than 8 TiB");
+    hipLaunchKernelGGL(copy_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, (const uint4v *)src,
+                       (uint4v *)dst, n);
     return check_launch("astraea_probe_copy");
 }
 

@@ -1,13 +1,20 @@
-// Row movers behind astraea_gather_rows and astraea_scatter_update, and the per-token S_LSE update
-// (paper, Algorithm 1: X_in[I_sel] in step 5, and the cache merge of steps 6-7).
+// Row movers behind astraea_gather_rows, astraea_scatter_update and astraea_kv_refresh, and the per-token
+// S_LSE update (paper, Algorithm 1: X_in[I_sel] in step 5, and the cache merge of steps 6-7).
 //
 // A token row (H*D elements, 6 KiB for 24 heads x 128 x bf16) is contiguous, so the copy is fully
-// coalesced without staging: one wavefront moves one row, each lane 16 bytes per step, all of a
-// lane's loads issued before its stores.  Unselected rows are never touched, which is exactly the
-// "reuse the cached result" half of the merge.  HBM-bound: 2 * row_bytes per selected token.
-// A source row is read once, so its loads carry the streaming hint (not kept in L2): 112 -> 88 us for
-// the 219 MB scatter at N = 118800 with cold caches, no worse with warm ones.  Stores stay plain: the
-// destination rows are read again by the next kernel.
+// coalesced without staging.  Shape: one 16-byte vector per thread and one wavefront per workgroup, i.e. a
+// workgroup moves 1 KiB of one row and ends; consecutive workgroups take consecutive pieces of a row, then
+// the next row.  Measured at N = 118800, k = 35640, caches flushed before each call, against the earlier
+// shape (one wavefront per whole row, 6 vectors per lane): scatter 88 -> 74 us, K/V refresh 185 -> 147 us,
+// gather 86 -> 72 us; the same holds for a dense 1 GiB copy (one vector per thread 6.2 - 6.6 TB/s, a
+// grid-stride loop 4.6, eight vectors per thread 5.4).  Pieces of 128 or 384 threads: 5 - 10 % slower; 256: worse
+// than the earlier shape.  Unselected rows are never touched, which is exactly the "reuse the cached result"
+// half of the merge.  HBM-bound: 2 * row_bytes per selected token.
+// A source row is read once, so its loads carry the streaming hint (not kept in L2).  Stores carry it when
+// both sides are rows of full-size buffers (the K/V refresh, the copy of the selected tokens' features): 172 ->
+// 148 us for the refresh.  Stores of compact rows stay plain (the next kernel reads them), and so do the
+// scatter's: its source was written by the kernel before it and is still in the caches, and with streaming
+// stores that case is slower (64 -> 70 us inside a layer-step).
 #include "common.h"
 
 namespace astraea {
@@ -15,46 +22,30 @@ namespace {
 
 typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
 
-constexpr int kRowsPerBlock = 4;      // one wave per row
-
 template <typename V> __device__ __forceinline__ V load_once(const V *p) { return __builtin_nontemporal_load(p); }
 
-// blockIdx.y picks one of up to two (destination, source) buffer pairs that share shape, strides and index list:
-// the K and the V cache of a layer are refreshed by one launch.
-template <typename V>
-__global__ __launch_bounds__(kRowsPerBlock *kWave) void move_rows_kernel(
+// blockIdx.x = row * pieces + piece; blockIdx.y picks one of up to two (destination, source) buffer pairs that
+// share shape, strides and index list: the K and the V cache of a layer are refreshed by one launch.
+// STREAM_DST is a template parameter because a run-time choice between the two kinds of store is merged by
+// the compiler into one plain store.
+template <typename V, bool STREAM_DST>
+__global__ __launch_bounds__(kWave) void move_rows_kernel(
     char *__restrict__ dst0, const char *__restrict__ src0, char *__restrict__ dst1, const char *__restrict__ src1,
     int64_t row_bytes, int64_t dst_stride, int64_t src_stride,
-    const int32_t *__restrict__ idx, int64_t k_sel, int64_t n_rows, int index_dst, int index_src)
+    const int32_t *__restrict__ idx, int64_t k_sel, int64_t n_rows, int index_dst, int index_src, int32_t pieces)
 {
     char *__restrict__ dst = blockIdx.y ? dst1 : dst0;
     const char *__restrict__ src = blockIdx.y ? src1 : src0;
-    const int lane = threadIdx.x & (kWave - 1);
-    const int64_t r = (int64_t)blockIdx.x * kRowsPerBlock + threadIdx.x / kWave;
-    if (r >= k_sel) return;
+    const int64_t r = blockIdx.x / (uint32_t)pieces;
+    const int64_t p = (int64_t)(blockIdx.x % (uint32_t)pieces) * kWave + threadIdx.x;
+    if (r >= k_sel || p >= row_bytes / (int64_t)sizeof(V)) return;
     const int64_t tok = idx[r];
     if ((uint64_t)tok >= (uint64_t)n_rows) return;      // an index outside the buffer moves nothing
     const V *s = reinterpret_cast<const V *>(src + (index_src ? tok : r) * src_stride);
     V *d = reinterpret_cast<V *>(dst + (index_dst ? tok : r) * dst_stride);
-    const int64_t nvec = row_bytes / (int64_t)sizeof(V);
-    // groups of 4, then 2, then 1 vectors per lane: every group's loads are issued before its stores
-    int64_t p = lane;
-#pragma unroll 1
-    for (; p + 3 * kWave < nvec; p += 4 * kWave) {
-        const V b0 = load_once(s + p), b1 = load_once(s + p + kWave), b2 = load_once(s + p + 2 * kWave),
-                b3 = load_once(s + p + 3 * kWave);
-        d[p] = b0;
-        d[p + kWave] = b1;
-        d[p + 2 * kWave] = b2;
-        d[p + 3 * kWave] = b3;
-    }
-    if (p + kWave < nvec) {
-        const V b0 = load_once(s + p), b1 = load_once(s + p + kWave);
-        d[p] = b0;
-        d[p + kWave] = b1;
-        p += 2 * kWave;
-    }
-    if (p < nvec) d[p] = load_once(s + p);
+    const V v = load_once(s + p);
+    if (STREAM_DST) __builtin_nontemporal_store(v, d + p);
+    else d[p] = v;
 }
 
 // lse_weight[idx[r]] = mean over heads of exp(min(lse[r, h] - ln N, 64)); one thread per selected token.
@@ -113,21 +104,29 @@ int launch_move_rows(void *dst, const void *src, int64_t row_bytes, int64_t dst_
                      bool index_src, hipStream_t stream, void *dst_b, const void *src_b)
 {
     if (k_sel == 0 || row_bytes == 0) return ASTRAEA_OK;
-    dim3 grid((unsigned)((k_sel + kRowsPerBlock - 1) / kRowsPerBlock), dst_b ? 2u : 1u), block(kRowsPerBlock * kWave);
     const uintptr_t all = (uintptr_t)dst | (uintptr_t)src | (uintptr_t)dst_b | (uintptr_t)src_b | (uintptr_t)row_bytes |
                           (uintptr_t)dst_stride_bytes | (uintptr_t)src_stride_bytes;
-    if (all % 16 == 0)
-        hipLaunchKernelGGL(move_rows_kernel<uint4v>, grid, block, 0, stream, (char *)dst, (const char *)src, (char *)dst_b,
-                           (const char *)src_b, row_bytes, dst_stride_bytes, src_stride_bytes, idx, k_sel, n_rows,
-                           (int)index_dst, (int)index_src);
-    else if (all % 4 == 0)
-        hipLaunchKernelGGL(move_rows_kernel<uint32_t>, grid, block, 0, stream, (char *)dst, (const char *)src, (char *)dst_b,
-                           (const char *)src_b, row_bytes, dst_stride_bytes, src_stride_bytes, idx, k_sel, n_rows,
-                           (int)index_dst, (int)index_src);
-    else
-        hipLaunchKernelGGL(move_rows_kernel<uint16_t>, grid, block, 0, stream, (char *)dst, (const char *)src, (char *)dst_b,
-                           (const char *)src_b, row_bytes, dst_stride_bytes, src_stride_bytes, idx, k_sel, n_rows,
-                           (int)index_dst, (int)index_src);
+    const int vec = all % 16 == 0 ? 16 : (all % 4 == 0 ? 4 : 2);
+    const int64_t pieces = (row_bytes / vec + kWave - 1) / kWave;
+    if (pieces > 2147483647LL / k_sel) return fail(ASTRAEA_ERR_INVALID, "astraea row move: k_sel * row pieces exceeds the grid limit");
+    dim3 grid((unsigned)(k_sel * pieces), dst_b ? 2u : 1u), block(kWave);
+#define ASTRAEA_MOVE(V, S)                                                                                              \
+    hipLaunchKernelGGL((move_rows_kernel<V, S>), grid, block, 0, stream, (char *)dst, (const char *)src, (char *)dst_b, \
+                       (const char *)src_b, row_bytes, dst_stride_bytes, src_stride_bytes, idx, k_sel, n_rows,         \
+                       (int)index_dst, (int)index_src, (int32_t)pieces)
+    // cache rows refreshed from rows of another full-size buffer: both sides come from and go to HBM
+    const bool stream_dst = index_dst && index_src;
+    if (vec == 16) {
+        if (stream_dst) ASTRAEA_MOVE(uint4v, true);
+        else ASTRAEA_MOVE(uint4v, false);
+    } else if (vec == 4) {
+        if (stream_dst) ASTRAEA_MOVE(uint32_t, true);
+        else ASTRAEA_MOVE(uint32_t, false);
+    } else {
+        if (stream_dst) ASTRAEA_MOVE(uint16_t, true);
+        else ASTRAEA_MOVE(uint16_t, false);
+    }
+#undef ASTRAEA_MOVE
     return check_launch("astraea row move");
 }
 
